@@ -1,0 +1,146 @@
+/* moe.h -- C ABI of the MI355X (gfx950) MoE-layer forward library.
+ *
+ * The library computes the forward pass of one Mixture-of-Experts layer as the
+ * DeepSpeed-MoE paper (arXiv 2201.05596) states it in Sec. 5.4: a gating
+ * function assigns tokens to experts, the tokens are sorted by assigned expert
+ * (dispatch), each expert's FFN runs on its tokens, and the expert outputs are
+ * scaled by the gate probability and put back in token order (combine).  As in
+ * Sec. 5.4 the one-hot/einsum formulation is replaced by a dense
+ * token-to-expert mapping table and explicit data-layout transforms.  The
+ * Residual-MoE variant of Sec. 4.1.1 adds a dense MLP branch to every token.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or synchronises.  All work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Tensors are row-major and densely packed; base pointers must be 16-byte
+ *     aligned.  Element type of x / xe / ye / out and of the FFN weights and
+ *     biases is `shape.dtype`; gate weights, gate bias, logits and gate_w are
+ *     always float; indices are int32_t.
+ *   - `shape` is a HOST pointer, read before the call returns.
+ *   - Return value: MOE_OK, or a negative moe_status_t.  On
+ *     MOE_ERR_INVALID_ARG / MOE_ERR_UNSUPPORTED / MOE_ERR_WORKSPACE nothing
+ *     was launched, no HIP call was made and no output was touched.
+ *     MOE_ERR_HIP reports a failed launch; outputs are then unspecified.
+ *   - `capacity` (rows per expert, C) is always given explicitly; the library
+ *     never derives it from a capacity factor.
+ *   - Non-finite gate logits give unspecified routing.
+ *   - Calls on one stream are ordered; two calls that share a workspace and
+ *     run concurrently on different streams race.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1,  /* null pointer, misaligned pointer, bad size        */
+    MOE_ERR_UNSUPPORTED = -2,  /* valid request outside what the kernels cover      */
+    MOE_ERR_WORKSPACE = -3,    /* ws is NULL or smaller than moe_workspace_bytes()  */
+    MOE_ERR_HIP = -4           /* a kernel launch failed                            */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+/* Shape of one MoE layer.  Limits: T >= 1, 1 <= E <= 1024, top_k in {1,2} and
+ * <= E, capacity >= 1, T*top_k and E*capacity below 2^31; d_model and d_ffn
+ * multiples of 8 (bf16) or 4 (f32).  `flags` must be 0. */
+typedef struct {
+    int32_t T;         /* tokens (paper: S)                                    */
+    int32_t d_model;   /* hidden size (paper: M)                               */
+    int32_t d_ffn;     /* expert FFN inner width                               */
+    int32_t E;         /* experts                                              */
+    int32_t top_k;     /* experts per token                                    */
+    int32_t capacity;  /* rows per expert (paper: c_e)                         */
+    int32_t dtype;     /* moe_dtype_t                                          */
+    int32_t residual;  /* 1: Residual-MoE (dense MLP branch added), else 0     */
+    int32_t flags;     /* reserved, 0                                          */
+} moe_shape_t;
+
+/* Upper bound, in bytes, of the workspace any entry point needs for this
+ * shape.  Returns 0 for an invalid shape.  Pure host arithmetic. */
+size_t moe_workspace_bytes(const moe_shape_t* shape);
+
+/* Static string for a status code. */
+const char* moe_status_string(int status);
+
+/* Library version, "major.minor". */
+const char* moe_version(void);
+
+/* moe_gate -- the fused gating function of Sec. 5.4: gate logits, softmax,
+ * top-k, the cumulative sum that gives each token its position inside its
+ * expert, the capacity cut, and the mapping tables.
+ *
+ *   x          [T,d]   tokens, or NULL to route from given logits
+ *   Wg         [d,E]   float gate weights (ignored when x == NULL)
+ *   bg         [E]     float gate bias or NULL
+ *   logits     [T,E]   float.  x == NULL: INPUT.  Otherwise OUTPUT,
+ *                      l[t,e] = bg[e] + sum_i x[t,i] Wg[i,e]; may be NULL.
+ *   expert_idx [T,k]   out: chosen experts, highest logit first; ties go to the
+ *                      lowest expert index
+ *   slot_idx   [T,k]   out: row inside the expert, or -1 if dropped.  The row
+ *                      is the number of earlier claims on that expert: claims
+ *                      are ordered by choice rank first (every first choice
+ *                      before any second choice), then by token index; a claim
+ *                      whose position is >= capacity is dropped.
+ *   gate_w     [T,k]   out: top-1: softmax probability of the chosen expert;
+ *                      top-2: the two chosen probabilities divided by their sum
+ *   expert_rows[E]     out: kept rows per expert (<= capacity)
+ *   slot_token [E,C]   out: token held by each row, -1 for rows >= expert_rows
+ *   ws                 workspace, >= moe_workspace_bytes(shape)
+ * Routing (expert_idx, slot_idx, expert_rows, slot_token) is a deterministic
+ * function of the fp32 logits. */
+int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg,
+             float* logits, int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
+             int32_t* expert_rows, int32_t* slot_token,
+             void* ws, size_t ws_bytes, void* stream);
+
+/* moe_dispatch -- first layout transform of Sec. 5.4 (replaces the sparse
+ * einsum that sorts tokens by expert): xe[e,c,:] = x[slot_token[e,c],:] for
+ * c < expert_rows[e].  Rows c >= expert_rows[e] of xe are left untouched. */
+int moe_dispatch(const moe_shape_t* shape, const void* x, const int32_t* slot_token,
+                 const int32_t* expert_rows, void* xe /* [E,C,d] */, void* stream);
+
+/* moe_expert_ffn -- the expert FFNs (Sec. 3.1: each expert is an FFN of the
+ * base model): for c < expert_rows[e]
+ *   ye[e,c,:] = gelu_tanh(xe[e,c,:] W1[e] + b1[e]) W2[e] + b2[e].
+ *   W1 [E,d,f], b1 [E,f] or NULL, W2 [E,f,d], b2 [E,d] or NULL.
+ * Rows c >= expert_rows[e] of ye are left untouched; weights of experts with
+ * no rows are not read. */
+int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expert_rows,
+                   const void* W1, const void* b1, const void* W2, const void* b2,
+                   void* ye /* [E,C,d] */, void* ws, size_t ws_bytes, void* stream);
+
+/* moe_combine -- second layout transform of Sec. 5.4 (replaces the final
+ * einsum; scales by the gate probability and restores token order):
+ *   out[t,:] = addend[t,:] + sum_j [slot_idx[t,j] >= 0] gate_w[t,j] ye[expert_idx[t,j], slot_idx[t,j], :]
+ * with fp32 accumulation.  addend ([T,d], same dtype) may be NULL (= 0).  A token
+ * whose choices were all dropped gets exactly addend (exactly 0 without one). */
+int moe_combine(const moe_shape_t* shape, const void* ye, const int32_t* expert_idx,
+                const int32_t* slot_idx, const float* gate_w, const void* addend,
+                void* out /* [T,d] */, void* stream);
+
+/* moe_layer_forward -- the whole layer behind one call (Sec. 5.4 fuses the gate
+ * and the layout transforms; Sec. 4.1.1 defines the residual branch):
+ *   out = combine(expert_ffn(dispatch(x))) [+ gelu_tanh(x Wd1 + bd1) Wd2 + bd2].
+ * Wd1 [d,f], bd1 [f] or NULL, Wd2 [f,d], bd2 [d] or NULL are required iff
+ * shape.residual.  The *_out pointers are optional (NULL) exports of the gate's
+ * results, shaped as in moe_gate.  No host synchronisation happens inside. */
+int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg,
+                      const void* W1, const void* b1, const void* W2, const void* b2,
+                      const void* Wd1, const void* bd1, const void* Wd2, const void* bd2,
+                      void* out /* [T,d] */,
+                      float* logits_out, int32_t* expert_idx_out, int32_t* slot_idx_out,
+                      float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out,
+                      void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

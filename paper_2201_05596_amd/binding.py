@@ -1,0 +1,161 @@
+"""ctypes binding of libmoe_hip.so: argument marshalling only.
+
+Every function here has the name and the argument order of the C entry point
+declared in include/moe.h and does nothing but check tensor device, dtype and
+contiguity, and pass raw device pointers plus the current HIP stream.  PyTorch
+is used for device memory and streams only; every step of the layer runs in the
+library's kernels.  There is no fallback: if the shared library is missing, or
+a call returns a non-zero status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_OK = 0
+ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_dispatch",
+                "moe_expert_ffn", "moe_combine", "moe_layer_forward")
+
+
+class MoeShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "d_model", "d_ffn", "E", "top_k", "capacity", "dtype", "residual", "flags")]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn} failed: status {status} ({text})")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmoe_hip.so (built by ``python -m paper_2201_05596_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2201_05596_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, st = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    sp = ctypes.POINTER(MoeShape)
+    lib.moe_workspace_bytes.restype = st
+    lib.moe_workspace_bytes.argtypes = [sp]
+    lib.moe_status_string.restype = ctypes.c_char_p
+    lib.moe_status_string.argtypes = [i32]
+    lib.moe_version.restype = ctypes.c_char_p
+    lib.moe_version.argtypes = []
+    lib.moe_gate.restype = i32
+    lib.moe_gate.argtypes = [sp] + [vp] * 9 + [vp, st, vp]
+    lib.moe_dispatch.restype = i32
+    lib.moe_dispatch.argtypes = [sp] + [vp] * 4 + [vp]
+    lib.moe_expert_ffn.restype = i32
+    lib.moe_expert_ffn.argtypes = [sp] + [vp] * 7 + [vp, st, vp]
+    lib.moe_combine.restype = i32
+    lib.moe_combine.argtypes = [sp] + [vp] * 6 + [vp]
+    lib.moe_layer_forward.restype = i32
+    lib.moe_layer_forward.argtypes = [sp] + [vp] * 18 + [vp, st, vp]
+    _lib = lib
+    return lib
+
+
+def make_shape(T: int, d_model: int, d_ffn: int, E: int, top_k: int, capacity: int, dtype, residual: bool = False) -> MoeShape:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: MOE_F32, torch.bfloat16: MOE_BF16}[dtype]
+    elif isinstance(dtype, str):
+        dtype = {"f32": MOE_F32, "bf16": MOE_BF16}[dtype]
+    return MoeShape(T, d_model, d_ffn, E, top_k, capacity, int(dtype), int(bool(residual)), 0)
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor required")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor required")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(fn: str, status: int) -> None:
+    if status != MOE_OK:
+        raise MoeError(fn, status, load_library().moe_status_string(status).decode())
+
+
+def _elem(shape: MoeShape) -> torch.dtype:
+    return torch.float32 if shape.dtype == MOE_F32 else torch.bfloat16
+
+
+def moe_workspace_bytes(shape: MoeShape) -> int:
+    return int(load_library().moe_workspace_bytes(ctypes.byref(shape)))
+
+
+def moe_version() -> str:
+    return load_library().moe_version().decode()
+
+
+def alloc_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:
+    """Device memory for the `ws` argument (plumbing: torch owns the allocation)."""
+    n = moe_workspace_bytes(shape)
+    if n == 0:
+        raise MoeError("moe_workspace_bytes", -1, "invalid shape")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def moe_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws) -> None:
+    i32, f32 = torch.int32, torch.float32
+    rc = load_library().moe_gate(
+        ctypes.byref(shape), _ptr(x, _elem(shape) if x is not None else None), _ptr(Wg, f32), _ptr(bg, f32),
+        _ptr(logits, f32), _ptr(expert_idx, i32), _ptr(slot_idx, i32), _ptr(gate_w, f32), _ptr(expert_rows, i32),
+        _ptr(slot_token, i32), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check("moe_gate", rc)
+
+
+def moe_dispatch(shape, x, slot_token, expert_rows, xe) -> None:
+    el = _elem(shape)
+    rc = load_library().moe_dispatch(ctypes.byref(shape), _ptr(x, el), _ptr(slot_token, torch.int32),
+                                     _ptr(expert_rows, torch.int32), _ptr(xe, el), _stream())
+    _check("moe_dispatch", rc)
+
+
+def moe_expert_ffn(shape, xe, expert_rows, W1, b1, W2, b2, ye, ws) -> None:
+    el = _elem(shape)
+    rc = load_library().moe_expert_ffn(
+        ctypes.byref(shape), _ptr(xe, el), _ptr(expert_rows, torch.int32), _ptr(W1, el), _ptr(b1, el), _ptr(W2, el),
+        _ptr(b2, el), _ptr(ye, el), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check("moe_expert_ffn", rc)
+
+
+def moe_combine(shape, ye, expert_idx, slot_idx, gate_w, addend, out) -> None:
+    el = _elem(shape)
+    rc = load_library().moe_combine(ctypes.byref(shape), _ptr(ye, el), _ptr(expert_idx, torch.int32),
+                                    _ptr(slot_idx, torch.int32), _ptr(gate_w, torch.float32), _ptr(addend, el),
+                                    _ptr(out, el), _stream())
+    _check("moe_combine", rc)
+
+
+def moe_layer_forward(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out,
+                      logits_out, expert_idx_out, slot_idx_out, gate_w_out, expert_rows_out, slot_token_out, ws) -> None:
+    el, i32, f32 = _elem(shape), torch.int32, torch.float32
+    rc = load_library().moe_layer_forward(
+        ctypes.byref(shape), _ptr(x, el), _ptr(Wg, f32), _ptr(bg, f32), _ptr(W1, el), _ptr(b1, el), _ptr(W2, el),
+        _ptr(b2, el), _ptr(Wd1, el), _ptr(bd1, el), _ptr(Wd2, el), _ptr(bd2, el), _ptr(out, el),
+        _ptr(logits_out, f32), _ptr(expert_idx_out, i32), _ptr(slot_idx_out, i32), _ptr(gate_w_out, f32),
+        _ptr(expert_rows_out, i32), _ptr(slot_token_out, i32),
+        _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check("moe_layer_forward", rc)

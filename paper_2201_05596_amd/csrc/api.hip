@@ -1,0 +1,206 @@
+// C ABI of the library: argument checks, workspace carving and launch sequencing.
+// Every check happens on the host before the first HIP call.
+#include "moe_internal.h"
+
+using namespace moe;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t esize(int dtype) { return dtype == MOE_F32 ? 4 : 2; }
+
+int check_shape(const moe_shape_t* s) {
+    if (!s) return MOE_ERR_INVALID_ARG;
+    if (s->T < 1 || s->d_model < 1 || s->d_ffn < 1 || s->E < 1 || s->capacity < 1) return MOE_ERR_INVALID_ARG;
+    if (s->top_k < 1 || s->top_k > s->E) return MOE_ERR_INVALID_ARG;
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (s->residual != 0 && s->residual != 1) return MOE_ERR_INVALID_ARG;
+    if (s->flags != 0) return MOE_ERR_INVALID_ARG;
+    if (s->top_k > 2 || s->E > 1024) return MOE_ERR_UNSUPPORTED;
+    const int mult = s->dtype == MOE_F32 ? 4 : 8;
+    if (s->d_model % mult || s->d_ffn % mult) return MOE_ERR_UNSUPPORTED;
+    if ((long long)s->T * s->top_k >= (1ll << 31) || (long long)s->E * s->capacity >= (1ll << 31))
+        return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+// Carving of the caller's workspace.  Offsets in bytes; every region 256-byte aligned.
+struct WsLayout {
+    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, slot_token, xe, h, ye, hd, dense, total;
+};
+
+WsLayout ws_layout(const moe_shape_t* s) {
+    WsLayout L{};
+    const size_t T = s->T, d = s->d_model, f = s->d_ffn, E = s->E, k = s->top_k, C = s->capacity;
+    const size_t es = esize(s->dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+    L.logits = take(T * E * 4);
+    L.hist = take(route_scratch_ints(s->T, s->E, s->top_k) * 4);
+    L.expert_idx = take(T * k * 4);
+    L.slot_idx = take(T * k * 4);
+    L.gate_w = take(T * k * 4);
+    L.rows = take(E * 4);
+    L.slot_token = take(E * C * 4);
+    L.xe = take(E * C * d * es);
+    L.h = take(E * C * f * es);
+    L.ye = take(E * C * d * es);
+    L.hd = take(s->residual ? T * f * es : 0);
+    L.dense = take(s->residual ? T * d * es : 0);
+    L.total = off;
+    return L;
+}
+
+template <typename T> inline T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+int check_ws(const moe_shape_t* s, const void* ws, size_t ws_bytes) {
+    if (!ws || !aligned16(ws) || ws_bytes < ws_layout(s).total) return MOE_ERR_WORKSPACE;
+    return MOE_OK;
+}
+
+// the two GEMMs of the expert FFN (or, with G = 1 and fixed rows, of the dense branch)
+int run_ffn(int dtype, int G, int max_rows, const int32_t* rows, int fixed_rows, int d, int f, const void* xin,
+            const void* W1, const void* b1, const void* W2, const void* b2, void* h, void* yout, hipStream_t st) {
+    GemmArgs a{};
+    a.A = xin; a.B = W1; a.bias = b1; a.out = h; a.rows = rows; a.row_map = nullptr;
+    a.fixed_rows = fixed_rows; a.max_rows = max_rows; a.G = G; a.K = d; a.N = f;
+    a.a_group_stride = max_rows; a.o_group_stride = max_rows; a.gelu = 1; a.dtype = dtype;
+    int rc = launch_gemm_simple(a, st);
+    if (rc != MOE_OK) return rc;
+    a.A = h; a.B = W2; a.bias = b2; a.out = yout; a.K = f; a.N = d; a.gelu = 0;
+    return launch_gemm_simple(a, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t moe_workspace_bytes(const moe_shape_t* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return ws_layout(shape).total;
+}
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported shape";
+        case MOE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case MOE_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+const char* moe_version(void) { return "0.1"; }
+
+int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
+             int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows, int32_t* slot_token,
+             void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (!expert_idx || !slot_idx || !gate_w || !expert_rows || !slot_token) return MOE_ERR_INVALID_ARG;
+    if (!x && !logits) return MOE_ERR_INVALID_ARG;
+    if (x && !Wg) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    rc = check_ws(shape, ws, ws_bytes);
+    if (rc != MOE_OK) return rc;
+
+    const WsLayout L = ws_layout(shape);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* lg = logits ? logits : at<float>(ws, L.logits);
+    if (x) {
+        rc = launch_gate_logits(x, shape->dtype, Wg, bg, lg, shape->T, shape->d_model, shape->E, st);
+        if (rc != MOE_OK) return rc;
+    }
+    return launch_route(lg, shape->T, shape->E, shape->top_k, shape->capacity, expert_idx, slot_idx, gate_w,
+                        expert_rows, slot_token, at<int32_t>(ws, L.hist), st);
+}
+
+int moe_dispatch(const moe_shape_t* shape, const void* x, const int32_t* slot_token, const int32_t* expert_rows,
+                 void* xe, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (!x || !slot_token || !expert_rows || !xe) return MOE_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(slot_token) || !aligned16(expert_rows) || !aligned16(xe)) return MOE_ERR_INVALID_ARG;
+    return launch_dispatch(x, shape->dtype, slot_token, expert_rows, xe, shape->E, shape->capacity, shape->d_model,
+                           static_cast<hipStream_t>(stream));
+}
+
+int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expert_rows, const void* W1,
+                   const void* b1, const void* W2, const void* b2, void* ye, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (!xe || !expert_rows || !W1 || !W2 || !ye) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {xe, expert_rows, W1, b1, W2, b2, ye};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    rc = check_ws(shape, ws, ws_bytes);
+    if (rc != MOE_OK) return rc;
+    const WsLayout L = ws_layout(shape);
+    return run_ffn(shape->dtype, shape->E, shape->capacity, expert_rows, 0, shape->d_model, shape->d_ffn, xe, W1, b1,
+                   W2, b2, at<void>(ws, L.h), ye, static_cast<hipStream_t>(stream));
+}
+
+int moe_combine(const moe_shape_t* shape, const void* ye, const int32_t* expert_idx, const int32_t* slot_idx,
+                const float* gate_w, const void* addend, void* out, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (!ye || !expert_idx || !slot_idx || !gate_w || !out) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {ye, expert_idx, slot_idx, gate_w, addend, out};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    return launch_combine(ye, shape->dtype, expert_idx, slot_idx, gate_w, addend, out, shape->T, shape->top_k,
+                          shape->capacity, shape->d_model, static_cast<hipStream_t>(stream));
+}
+
+int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, const void* W1,
+                      const void* b1, const void* W2, const void* b2, const void* Wd1, const void* bd1, const void* Wd2,
+                      const void* bd2, void* out, float* logits_out, int32_t* expert_idx_out, int32_t* slot_idx_out,
+                      float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out, void* ws, size_t ws_bytes,
+                      void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (!x || !Wg || !W1 || !W2 || !out) return MOE_ERR_INVALID_ARG;
+    if (shape->residual && (!Wd1 || !Wd2)) return MOE_ERR_INVALID_ARG;
+    if (!shape->residual && (Wd1 || Wd2 || bd1 || bd2)) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out, logits_out, expert_idx_out,
+                          slot_idx_out, gate_w_out, expert_rows_out, slot_token_out};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    rc = check_ws(shape, ws, ws_bytes);
+    if (rc != MOE_OK) return rc;
+
+    const WsLayout L = ws_layout(shape);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = shape->T, d = shape->d_model, f = shape->d_ffn, E = shape->E, k = shape->top_k, C = shape->capacity;
+    const int dt = shape->dtype;
+
+    float* logits = logits_out ? logits_out : at<float>(ws, L.logits);
+    int32_t* expert_idx = expert_idx_out ? expert_idx_out : at<int32_t>(ws, L.expert_idx);
+    int32_t* slot_idx = slot_idx_out ? slot_idx_out : at<int32_t>(ws, L.slot_idx);
+    float* gate_w = gate_w_out ? gate_w_out : at<float>(ws, L.gate_w);
+    int32_t* rows = expert_rows_out ? expert_rows_out : at<int32_t>(ws, L.rows);
+    int32_t* slot_token = slot_token_out ? slot_token_out : at<int32_t>(ws, L.slot_token);
+
+    rc = launch_gate_logits(x, dt, Wg, bg, logits, T, d, E, st);
+    if (rc != MOE_OK) return rc;
+    rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, at<int32_t>(ws, L.hist), st);
+    if (rc != MOE_OK) return rc;
+    rc = launch_dispatch(x, dt, slot_token, rows, at<void>(ws, L.xe), E, C, d, st);
+    if (rc != MOE_OK) return rc;
+    rc = run_ffn(dt, E, C, rows, 0, d, f, at<void>(ws, L.xe), W1, b1, W2, b2, at<void>(ws, L.h), at<void>(ws, L.ye), st);
+    if (rc != MOE_OK) return rc;
+    const void* addend = nullptr;
+    if (shape->residual) {
+        rc = run_ffn(dt, 1, T, nullptr, T, d, f, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd), at<void>(ws, L.dense), st);
+        if (rc != MOE_OK) return rc;
+        addend = at<void>(ws, L.dense);
+    }
+    return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
+}
+
+}  // extern "C"

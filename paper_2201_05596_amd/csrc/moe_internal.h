@@ -1,0 +1,87 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kRouteTokens = 256;    // tokens per block in the routing kernels
+
+// ---- bf16 <-> f32 on raw 16-bit patterns -------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) {
+    return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+// gelu_tanh(z) = 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))), with
+// tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 / rcp units.
+__device__ __forceinline__ float gelu_tanh(float z) {
+    const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    const float t = __builtin_amdgcn_exp2f(u * 2.8853900817779268f);   // exp(2u)
+    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f);
+    return 0.5f * z * (1.0f + th);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {
+    static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- launchers (each returns MOE_OK or MOE_ERR_HIP) ---------------------------------------
+
+// logits[t,e] = bg[e] + sum_i x[t,i] Wg[i,e]
+int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* bg, float* logits,
+                       int T, int d, int E, hipStream_t s);
+
+// number of int32 the routing kernels need as scratch
+size_t route_scratch_ints(int T, int E, int k);
+
+// softmax + top-k + capacity slots from fp32 logits
+int launch_route(const float* logits, int T, int E, int k, int C,
+                 int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
+                 int32_t* expert_rows, int32_t* slot_token, int32_t* scratch, hipStream_t s);
+
+int launch_dispatch(const void* x, int dtype, const int32_t* slot_token, const int32_t* expert_rows,
+                    void* xe, int E, int C, int d, hipStream_t s);
+
+int launch_combine(const void* ye, int dtype, const int32_t* expert_idx, const int32_t* slot_idx,
+                   const float* gate_w, const void* addend, void* out,
+                   int T, int k, int C, int d, hipStream_t s);
+
+// Grouped GEMM  out[g, r, :] = epi( A[row(g,r), :] . B[g] + bias[g] )  for r < rows(g).
+struct GemmArgs {
+    const void* A;            // activations, row-major, leading dimension K
+    const void* B;            // [G, K, N] weights
+    const void* bias;         // [G, N] or nullptr
+    void* out;                // row-major, leading dimension N
+    const int32_t* rows;      // [G] device row counts, or nullptr -> fixed_rows for every group
+    const int32_t* row_map;   // [G, max_rows] A-row index per (g, r) (negative = skip), or nullptr
+    int32_t fixed_rows;
+    int32_t max_rows;         // upper bound of rows(g): sizes the grid
+    int32_t G, K, N;
+    int64_t a_group_stride;   // in rows; A-row of (g, r) = g*a_group_stride + r when row_map == nullptr
+    int64_t o_group_stride;   // in rows; out-row of (g, r) = g*o_group_stride + r
+    int32_t gelu;             // 1: gelu_tanh after the bias
+    int32_t dtype;            // element type of A, B, bias, out
+};
+int launch_gemm_simple(const GemmArgs& a, hipStream_t s);
+
+}  // namespace moe

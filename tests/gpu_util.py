@@ -1,0 +1,102 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the binding,
+run the oracle on host copies of the very same tensors, compare."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from oracle import moe_oracle as orc
+from workloads import LayerInputs, MoEConfig
+from workloads.generate import to_f32_numpy
+
+TOL = {"f32": 1e-4, "bf16": 1.5e-2}        # max|delta| <= TOL * max|ref|
+GATE_W_ATOL = 1e-6
+LOGIT_RTOL = 1e-5                          # max|delta l| <= LOGIT_RTOL * max|l|
+
+
+def amd():
+    import paper_2201_05596_amd as m
+    return m
+
+
+def host(inp: LayerInputs) -> Dict[str, Optional[np.ndarray]]:
+    return {k: to_f32_numpy(v) for k, v in inp.tensors().items()}
+
+
+def gpu_forward(inp: LayerInputs, capacity: Optional[int] = None) -> Dict[str, torch.Tensor]:
+    m = amd()
+    cfg = inp.cfg
+    C = cfg.capacity if capacity is None else capacity
+    layer = m.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, C, cfg.dtype, inp.Wg, inp.bg, inp.W1, inp.b1,
+                       inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)
+    out = layer(inp.x)
+    torch.cuda.synchronize()
+    res = dict(layer.routing)
+    res["out"] = out
+    return res
+
+
+def gpu_route(logits: torch.Tensor, k: int, C: int) -> Dict[str, torch.Tensor]:
+    """moe_gate with x == NULL: routing from given fp32 logits."""
+    m = amd()
+    T, E = logits.shape
+    dev = logits.device
+    shape = m.make_shape(T, 8, 8, E, k, C, "bf16")
+    ws = m.alloc_workspace(shape, dev)
+    i32 = torch.int32
+    r = dict(expert_idx=torch.full((T, k), -7, dtype=i32, device=dev),
+             slot_idx=torch.full((T, k), -7, dtype=i32, device=dev),
+             gate_w=torch.full((T, k), -7.0, dtype=torch.float32, device=dev),
+             expert_rows=torch.full((E,), -7, dtype=i32, device=dev),
+             slot_token=torch.full((E, C), -7, dtype=i32, device=dev))
+    m.moe_gate(shape, None, None, None, logits, r["expert_idx"], r["slot_idx"], r["gate_w"], r["expert_rows"],
+               r["slot_token"], ws)
+    torch.cuda.synchronize()
+    return r
+
+
+def assert_routing_equal(gpu: Dict[str, torch.Tensor], ref: Dict[str, np.ndarray]) -> None:
+    for name in ("expert_idx", "slot_idx", "expert_rows", "slot_token"):
+        g = gpu[name].cpu().numpy()
+        assert g.shape == ref[name].shape, name
+        assert np.array_equal(g, ref[name]), f"{name} differs at {np.argwhere(g != ref[name])[:5].tolist()}"
+    gw = gpu["gate_w"].cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(gw - ref["gate_w"])) <= GATE_W_ATOL
+
+
+def assert_close(gpu_out: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "out") -> float:
+    g = gpu_out.detach().to("cpu").to(torch.float64).numpy()
+    scale = float(np.max(np.abs(ref)))
+    err = float(np.max(np.abs(g - ref)))
+    assert np.all(np.isfinite(g)), f"{what}: non-finite values"
+    assert err <= TOL[dtype] * scale, f"{what}: max|delta|={err:.3e} > {TOL[dtype]:.1e} * {scale:.3e}"
+    return err / scale if scale > 0 else 0.0
+
+
+def check_layer(inp: LayerInputs, capacity: Optional[int] = None) -> Dict[str, float]:
+    """Full-layer parity: logits within tolerance of the oracle's own; then the
+    oracle evaluates the rest of the layer on the GPU's fp32 logits, routing must
+    match bit for bit and the output within the dtype's tolerance."""
+    cfg = inp.cfg
+    C = cfg.capacity if capacity is None else capacity
+    res = gpu_forward(inp, C)
+    h = host(inp)
+    own = orc.gate_logits(h["x"], h["Wg"], h.get("bg"))
+    gl = res["logits"].cpu().numpy()
+    lerr = float(np.max(np.abs(gl.astype(np.float64) - own)))
+    assert lerr <= LOGIT_RTOL * float(np.max(np.abs(own))), f"logits off by {lerr:.3e}"
+    ref = orc.moe_layer_forward(h["x"], h["Wg"], h.get("bg"), h["W1"], h["b1"], h["W2"], h["b2"], cfg.top_k, C,
+                                Wd1=h.get("Wd1"), bd1=h.get("bd1"), Wd2=h.get("Wd2"), bd2=h.get("bd2"), logits=gl)
+    assert_routing_equal(res, ref)
+    rel = assert_close(res["out"], ref["out"], cfg.dtype)
+    if not cfg.residual:
+        dropped = np.all(ref["slot_idx"] < 0, axis=1)
+        if dropped.any():
+            go = res["out"].cpu().to(torch.float32).numpy()
+            assert np.all(go[dropped] == 0.0), "fully dropped tokens must be exactly zero"
+    own_route = orc.gate(own, cfg.top_k, C)
+    flips = int(np.sum(np.any(own_route["expert_idx"] != ref["expert_idx"], axis=1)))
+    return {"rel_err": rel, "logit_err": lerr, "route_flips_vs_own_logits": flips,
+            "kept": int(ref["expert_rows"].sum()), "dropped_tokens": int(np.all(ref["slot_idx"] < 0, axis=1).sum())}

@@ -1,0 +1,197 @@
+"""GPU parity tests: every C-ABI entry point against the CPU oracle on the same
+seeded inputs.  Routing is compared bit for bit on identical fp32 logits;
+floating-point outputs within max|delta| <= tol * max|ref| (1e-4 fp32, 1.5e-2
+bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as orc
+from tests import gpu_util as U
+from workloads import CONFIGS, make_inputs, make_logits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+# ------------------------------------------------------------------ routing from logits
+
+@pytest.mark.parametrize("kind", ["normal", "ties", "equal", "hot", "zipf"])
+@pytest.mark.parametrize("k,E,C,T", [
+    (1, 8, 32, 256), (1, 128, 64, 8192), (1, 128, 1, 64), (2, 64, 640, 16384),
+    (1, 1, 5, 9), (2, 2, 3, 10), (1, 3, 7, 63), (2, 3, 7, 65), (1, 64, 3, 257), (2, 128, 2, 1000),
+    (1, 200, 4, 777), (2, 1024, 1, 300), (1, 32, 256, 8192), (2, 8, 100000, 513),
+])
+def test_gate_routing_bit_exact(kind, k, E, C, T):
+    print(f"case kind={kind} k={k} E={E} C={C} T={T}", flush=True)
+    logits = make_logits(T, E, seed=T + 3 * E + k, kind=kind, device=DEV)
+    res = U.gpu_route(logits, k, C)
+    ref = orc.gate(logits.cpu().numpy(), k, C)
+    U.assert_routing_equal(res, ref)
+
+
+def test_gate_routing_deterministic():
+    logits = make_logits(5000, 64, seed=1, kind="zipf", device=DEV)
+    a = U.gpu_route(logits, 2, 50)
+    b = U.gpu_route(logits, 2, 50)
+    for n in a:
+        assert torch.equal(a[n], b[n]), n
+
+
+# ------------------------------------------------------------------ gate logits
+
+@pytest.mark.parametrize("dtype,T,d,E,bias", [("f32", 256, 64, 8, False), ("bf16", 1000, 1024, 128, False),
+                                              ("bf16", 77, 2048, 128, True), ("bf16", 300, 520, 64, True),
+                                              ("f32", 33, 100, 3, True), ("bf16", 129, 256, 300, False)])
+def test_gate_logits(dtype, T, d, E, bias):
+    m = U.amd()
+    g = torch.Generator(device=DEV).manual_seed(T + d)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = torch.randn((T, d), generator=g, device=DEV).to(tdt)
+    Wg = 0.02 * torch.randn((d, E), generator=g, device=DEV)
+    bg = torch.randn((E,), generator=g, device=DEV) if bias else None
+    shape = m.make_shape(T, d, 8, E, 1, 4, dtype)
+    ws = m.alloc_workspace(shape, DEV)
+    i32 = torch.int32
+    logits = torch.empty((T, E), dtype=torch.float32, device=DEV)
+    outs = [torch.empty((T, 1), dtype=i32, device=DEV), torch.empty((T, 1), dtype=i32, device=DEV),
+            torch.empty((T, 1), dtype=torch.float32, device=DEV), torch.empty((E,), dtype=i32, device=DEV),
+            torch.empty((E, 4), dtype=i32, device=DEV)]
+    m.moe_gate(shape, x, Wg, bg, logits, *outs, ws)
+    torch.cuda.synchronize()
+    ref = orc.gate_logits(x.float().cpu().numpy(), Wg.cpu().numpy(), None if bg is None else bg.cpu().numpy())
+    err = np.max(np.abs(logits.cpu().numpy().astype(np.float64) - ref))
+    assert err <= U.LOGIT_RTOL * np.max(np.abs(ref)), err
+
+
+# ------------------------------------------------------------------ dispatch / ffn / combine
+
+def _routing_on_device(ref, dev=DEV):
+    return {k: torch.from_numpy(np.ascontiguousarray(ref[k])).to(dev) for k in
+            ("expert_idx", "slot_idx", "expert_rows", "slot_token")}
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k,C", [("f32", 256, 64, 8, 1, 32), ("bf16", 1000, 1024, 16, 2, 70),
+                                             ("bf16", 64, 2048, 128, 1, 1), ("bf16", 300, 264, 5, 2, 1000)])
+def test_dispatch_exact_and_combine(dtype, T, d, E, k, C):
+    m = U.amd()
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(T)
+    x = torch.randn((T, d), generator=g, device=DEV).to(tdt)
+    ref = orc.gate(make_logits(T, E, seed=T, kind="zipf").numpy(), k, C)
+    r = _routing_on_device(ref)
+    shape = m.make_shape(T, d, 8, E, k, C, dtype)
+    canary = 123.0
+    xe = torch.full((E, C, d), canary, dtype=tdt, device=DEV)
+    m.moe_dispatch(shape, x, r["slot_token"], r["expert_rows"], xe)
+    torch.cuda.synchronize()
+    xe_ref = orc.dispatch(x.float().cpu().numpy(), ref["slot_token"])
+    xe_h = xe.float().cpu().numpy()
+    filled = ref["slot_token"] >= 0
+    assert np.array_equal(xe_h[filled], xe_ref[filled].astype(np.float32))         # data movement: exact
+    assert np.all(xe_h[~filled] == canary)                                          # untouched rows stay untouched
+    # combine on a random ye, with and without addend
+    ye = torch.randn((E, C, d), generator=g, device=DEV).to(tdt)
+    gw = torch.rand((T, k), generator=g, device=DEV)
+    addend = torch.randn((T, d), generator=g, device=DEV).to(tdt)
+    for add in (None, addend):
+        out = torch.empty((T, d), dtype=tdt, device=DEV)
+        m.moe_combine(shape, ye, r["expert_idx"], r["slot_idx"], gw, add, out)
+        torch.cuda.synchronize()
+        oref = orc.combine(ye.float().cpu().numpy(), ref["expert_idx"], ref["slot_idx"],
+                           gw.cpu().numpy().astype(np.float64), None if add is None else add.float().cpu().numpy())
+        U.assert_close(out, oref, dtype, "combine")
+        drop = np.all(ref["slot_idx"] < 0, axis=1)
+        if drop.any():
+            expect = np.zeros((int(drop.sum()), d), np.float32) if add is None else add.float().cpu().numpy()[drop]
+            assert np.array_equal(out.float().cpu().numpy()[drop], expect)
+
+
+@pytest.mark.parametrize("dtype,d,f,E,C,bias", [("f32", 64, 256, 8, 32, True), ("bf16", 256, 1024, 6, 70, True),
+                                                ("bf16", 1024, 4096, 4, 64, False), ("bf16", 2048, 8192, 6, 1, True),
+                                                ("bf16", 264, 520, 3, 130, True)])
+def test_expert_ffn(dtype, d, f, E, C, bias):
+    m = U.amd()
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(d + f)
+    rows = torch.randint(0, C + 1, (E,), generator=g, device=DEV).to(torch.int32)
+    rows[0] = C
+    if E > 2:
+        rows[1] = 0
+    xe = torch.randn((E, C, d), generator=g, device=DEV).to(tdt)
+    W1 = (0.02 * torch.randn((E, d, f), generator=g, device=DEV)).to(tdt)
+    W2 = (0.02 * torch.randn((E, f, d), generator=g, device=DEV)).to(tdt)
+    b1 = (0.1 * torch.randn((E, f), generator=g, device=DEV)).to(tdt) if bias else None
+    b2 = (0.1 * torch.randn((E, d), generator=g, device=DEV)).to(tdt) if bias else None
+    shape = m.make_shape(8, d, f, E, 1, C, dtype)
+    ws = m.alloc_workspace(shape, DEV)
+    canary = 77.0
+    ye = torch.full((E, C, d), canary, dtype=tdt, device=DEV)
+    m.moe_expert_ffn(shape, xe, rows, W1, b1, W2, b2, ye, ws)
+    torch.cuda.synchronize()
+    f32 = lambda t: None if t is None else t.float().cpu().numpy()
+    rows_h = rows.cpu().numpy()
+    ref = orc.expert_ffn(f32(xe).astype(np.float64), rows_h, f32(W1), f32(b1), f32(W2), f32(b2))
+    ye_h = ye.float().cpu().numpy()
+    valid = np.arange(C)[None, :] < rows_h[:, None]
+    assert np.all(ye_h[~valid] == canary)
+    scale = np.max(np.abs(ref[valid]))
+    assert np.max(np.abs(ye_h[valid] - ref[valid])) <= U.TOL[dtype] * scale
+
+
+# ------------------------------------------------------------------ whole layer
+
+def test_layer_c1_full():
+    stats = U.check_layer(make_inputs(CONFIGS["c1"], DEV, bias_std=0.0))
+    print("c1", stats, flush=True)
+    assert stats["dropped_tokens"] > 0
+
+
+def test_layer_c1_with_biases():
+    U.check_layer(make_inputs(CONFIGS["c1"], DEV, bias_std=0.05))
+
+
+REDUCED = {
+    # same structure as the full configurations, fewer experts/tokens so the fp64 oracle stays fast
+    "c2r": CONFIGS["c2"].scaled(name="c2r", T=1000, E=16, capacity_factor=1.0),
+    "c3r": CONFIGS["c3a"].scaled(name="c3r", T=900, E=8, d_ffn=2048),
+    "c4r": CONFIGS["c4"].scaled(name="c4r", E=32, d_ffn=4096),
+    "c5r": CONFIGS["c5"].scaled(name="c5r", T=1100, E=8, d_model=512, d_ffn=2048),
+}
+
+
+@pytest.mark.parametrize("name", sorted(REDUCED))
+@pytest.mark.parametrize("bias_std", [0.0, 0.05])
+def test_layer_reduced(name, bias_std):
+    print(f"case {name} bias_std={bias_std}", flush=True)
+    stats = U.check_layer(make_inputs(REDUCED[name], DEV, bias_std=bias_std))
+    print(name, stats, flush=True)
+
+
+def test_layer_ragged_sizes():
+    cfg = CONFIGS["c2"].scaled(name="ragged", T=333, d_model=264, d_ffn=520, E=5, top_k=2, capacity_factor=0.9)
+    U.check_layer(make_inputs(cfg, DEV, bias_std=0.05))
+
+
+def test_layer_single_expert_is_dense_ffn():
+    cfg = CONFIGS["c2"].scaled(name="e1", T=200, d_model=256, d_ffn=512, E=1, capacity_factor=1.0)
+    stats = U.check_layer(make_inputs(cfg, DEV, bias_std=0.05))
+    assert stats["dropped_tokens"] == 0
+
+
+def test_layer_deterministic():
+    inp = make_inputs(REDUCED["c5r"], DEV)
+    a = U.gpu_forward(inp)["out"].clone()
+    b = U.gpu_forward(inp)["out"].clone()
+    assert torch.equal(a, b)
+
+
+def test_residual_with_zero_experts_equals_dense_branch():
+    cfg = REDUCED["c3r"]
+    inp = make_inputs(cfg, DEV, bias_std=0.05)
+    for t in (inp.W1, inp.b1, inp.W2, inp.b2):
+        t.zero_()
+    res = U.gpu_forward(inp)
+    h = U.host(inp)
+    ref = orc.ffn(h["x"], h["Wd1"], h["bd1"], h["Wd2"], h["bd2"])
+    U.assert_close(res["out"], ref, cfg.dtype)

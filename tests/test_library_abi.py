@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the header declares, sizes its workspace sanely, and rejects bad
+arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2201_05596_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = _declared()
+    assert set(names) == set(B.ENTRY_POINTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    lib = B.load_library()
+    assert B.moe_version() == "0.1"
+    assert lib.moe_status_string(0) == b"ok"
+    for code in (-1, -2, -3, -4, 99):
+        assert len(lib.moe_status_string(code)) > 0
+
+
+def test_workspace_bytes():
+    s = B.make_shape(8192, 1024, 4096, 128, 1, 64, "bf16")
+    n = B.moe_workspace_bytes(s)
+    # at least logits + xe + h + ye
+    assert n >= 8192 * 128 * 4 + 128 * 64 * (1024 * 2 + 4096) * 2
+    assert n % 256 == 0
+    r = B.make_shape(8192, 1024, 4096, 32, 1, 256, "bf16", residual=True)
+    assert B.moe_workspace_bytes(r) > B.moe_workspace_bytes(B.make_shape(8192, 1024, 4096, 32, 1, 256, "bf16"))
+    assert B.moe_workspace_bytes(B.make_shape(0, 1024, 4096, 128, 1, 64, "bf16")) == 0
+
+
+BAD_SHAPES = [
+    (dict(T=0), -1), (dict(E=0), -1), (dict(capacity=0), -1), (dict(top_k=0), -1), (dict(top_k=200), -1),
+    (dict(dtype=5), -1), (dict(residual=2), -1), (dict(flags=1), -1),
+    (dict(top_k=3), -2), (dict(E=2048), -2), (dict(d_model=1028), -2), (dict(d_ffn=4100), -2),
+]
+
+
+@pytest.mark.parametrize("patch,code", BAD_SHAPES)
+def test_bad_shapes_rejected_without_launch(patch, code):
+    lib = B.load_library()
+    base = dict(T=8192, d_model=1024, d_ffn=4096, E=128, top_k=1, capacity=64, dtype=1, residual=0, flags=0)
+    base.update(patch)
+    s = B.MoeShape(**base)
+    fake = 0x1000          # aligned, never dereferenced: the call must fail before any launch
+    assert lib.moe_gate(ctypes.byref(s), *([fake] * 9), fake, 1 << 40, None) == code
+    assert lib.moe_dispatch(ctypes.byref(s), fake, fake, fake, fake, None) == code
+    assert lib.moe_expert_ffn(ctypes.byref(s), *([fake] * 7), fake, 1 << 40, None) == code
+    assert lib.moe_combine(ctypes.byref(s), *([fake] * 6), None) == code
+    assert lib.moe_layer_forward(ctypes.byref(s), *([fake] * 18), fake, 1 << 40, None) == code
+
+
+def test_null_misaligned_and_short_workspace():
+    lib = B.load_library()
+    s = B.make_shape(256, 64, 256, 8, 1, 32, "f32")
+    fake, odd = 0x1000, 0x1004
+    need = B.moe_workspace_bytes(s)
+    assert lib.moe_gate(None, *([fake] * 9), fake, need, None) == -1
+    assert lib.moe_gate(ctypes.byref(s), fake, fake, None, fake, None, fake, fake, fake, fake, fake, need, None) == -1
+    assert lib.moe_gate(ctypes.byref(s), None, None, None, None, fake, fake, fake, fake, fake, fake, need, None) == -1
+    assert lib.moe_gate(ctypes.byref(s), odd, *([fake] * 8), fake, need, None) == -1
+    assert lib.moe_gate(ctypes.byref(s), *([fake] * 9), fake, need - 1, None) == -3
+    assert lib.moe_gate(ctypes.byref(s), *([fake] * 9), None, need, None) == -3
+    assert lib.moe_expert_ffn(ctypes.byref(s), *([fake] * 7), fake, 16, None) == -3
+    assert lib.moe_combine(ctypes.byref(s), fake, fake, fake, fake, odd, fake, None) == -1
+    # dense-branch weights must come with residual = 1 and only then
+    assert lib.moe_layer_forward(ctypes.byref(s), *([fake] * 7), fake, None, fake, None, *([fake] * 7), fake, need, None) == -1
+    r = B.make_shape(256, 64, 256, 8, 1, 32, "f32", residual=True)
+    args = [fake] * 7 + [None, None, None, None] + [fake] * 7
+    assert lib.moe_layer_forward(ctypes.byref(r), *args, fake, B.moe_workspace_bytes(r), None) == -1
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    s = B.make_shape(4, 8, 8, 2, 1, 2, "f32")
+    x = torch.zeros((4, 8))
+    with pytest.raises(ValueError):
+        B.moe_dispatch(s, x, x, x, x)
