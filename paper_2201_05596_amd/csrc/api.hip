@@ -26,15 +26,45 @@ int check_shape(const moe_shape_t* s) {
     return MOE_OK;
 }
 
+// Tile shapes and split-K factor of the two expert GEMMs (bf16 MFMA path).
+struct FfnPlan {
+    bool mfma;          // false: plain fp32-ALU GEMM (fp32 layers)
+    int MT, NW1, NW2;   // row tile; waves per work-group of GEMM-1 / GEMM-2
+    int ksplit2;        // split-K factor of GEMM-2 (1 = none)
+};
+
+FfnPlan plan_ffn(const moe_shape_t* s) {
+    FfnPlan p{};
+    p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
+    p.ksplit2 = 1;
+    if (!p.mfma) return p;
+    wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
+    int mt2;
+    wsgemm_pick_tile(s->capacity, s->E, s->d_model, &mt2, &p.NW2);
+    // GEMM-2 has few output columns; when that leaves the chip short of waves, split K
+    const long long touched = s->E < (long long)s->T * s->top_k ? s->E : (long long)s->T * s->top_k;
+    const long long m_tiles = (s->capacity + p.MT - 1) / p.MT;
+    const long long waves = touched * ((s->d_model + 127) / 128) * m_tiles;
+    if (waves < 1024) {
+        const int chunks = (s->d_ffn + wsgemm_chunk_k(p.MT) - 1) / wsgemm_chunk_k(p.MT);
+        long long ks = (2048 + waves - 1) / waves;
+        if (ks > 8) ks = 8;
+        if (ks > chunks) ks = chunks;
+        p.ksplit2 = (int)(ks < 1 ? 1 : ks);
+    }
+    return p;
+}
+
 // Carving of the caller's workspace.  Offsets in bytes; every region 256-byte aligned.
 struct WsLayout {
-    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, slot_token, xe, h, ye, hd, dense, total;
+    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, slot_token, xe, h, ye, hd, dense, partial, total;
 };
 
 WsLayout ws_layout(const moe_shape_t* s) {
     WsLayout L{};
     const size_t T = s->T, d = s->d_model, f = s->d_ffn, E = s->E, k = s->top_k, C = s->capacity;
     const size_t es = esize(s->dtype);
+    const FfnPlan plan = plan_ffn(s);
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
     L.logits = take(T * E * 4);
@@ -44,11 +74,12 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.gate_w = take(T * k * 4);
     L.rows = take(E * 4);
     L.slot_token = take(E * C * 4);
-    L.xe = take(E * C * d * es);
+    L.xe = take(plan.mfma ? 0 : E * C * d * es);       // the MFMA path gathers rows inside GEMM-1
     L.h = take(E * C * f * es);
     L.ye = take(E * C * d * es);
     L.hd = take(s->residual ? T * f * es : 0);
-    L.dense = take(s->residual ? T * d * es : 0);
+    L.dense = take(s->residual && !plan.mfma ? T * d * es : 0);
+    L.partial = take(plan.ksplit2 > 1 ? (size_t)plan.ksplit2 * E * C * d * 4 : 0);
     L.total = off;
     return L;
 }
@@ -60,9 +91,9 @@ int check_ws(const moe_shape_t* s, const void* ws, size_t ws_bytes) {
     return MOE_OK;
 }
 
-// the two GEMMs of the expert FFN (or, with G = 1 and fixed rows, of the dense branch)
-int run_ffn(int dtype, int G, int max_rows, const int32_t* rows, int fixed_rows, int d, int f, const void* xin,
-            const void* W1, const void* b1, const void* W2, const void* b2, void* h, void* yout, hipStream_t st) {
+// the two GEMMs of an FFN on the plain fp32-ALU kernel (fp32 layers)
+int run_ffn_simple(int dtype, int G, int max_rows, const int32_t* rows, int fixed_rows, int d, int f, const void* xin,
+                   const void* W1, const void* b1, const void* W2, const void* b2, void* h, void* yout, hipStream_t st) {
     GemmArgs a{};
     a.A = xin; a.B = W1; a.bias = b1; a.out = h; a.rows = rows; a.row_map = nullptr;
     a.fixed_rows = fixed_rows; a.max_rows = max_rows; a.G = G; a.K = d; a.N = f;
@@ -71,6 +102,63 @@ int run_ffn(int dtype, int G, int max_rows, const int32_t* rows, int fixed_rows,
     if (rc != MOE_OK) return rc;
     a.A = h; a.B = W2; a.bias = b2; a.out = yout; a.K = f; a.N = d; a.gelu = 0;
     return launch_gemm_simple(a, st);
+}
+
+inline const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
+inline uint16_t* u16(void* p) { return static_cast<uint16_t*>(p); }
+
+// Expert GEMM-1 on the MFMA kernel: h[e, r, :] = gelu_tanh(A_row(e, r) W1[e] + b1[e]).
+// row_map == nullptr: A rows are xin[e*C + r]; otherwise xin[row_map[e*C + r]] (dispatch fused in).
+int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, const int32_t* row_map,
+                     const int32_t* rows, const void* W1, const void* b1, void* h, hipStream_t st) {
+    WsGemmArgs a{};
+    a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.row_map = row_map;
+    a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
+    a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
+    return launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, st);
+}
+
+// Expert GEMM-2 on the MFMA kernel.  scatter == false: ye[e, r, :] = h[e, r, :] W2[e] + b2[e].
+// scatter == true (top-1): out[token(e, r), :] = gate_w[token] * (...), rows of dropped tokens zeroed.
+int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, const int32_t* rows, const void* W2,
+                     const void* b2, bool scatter, const int32_t* slot_token, const int32_t* slot_idx,
+                     const float* gate_w, void* dst, float* partial, hipStream_t st) {
+    WsGemmArgs a{};
+    a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.row_map = nullptr;
+    a.max_rows = s->capacity; a.G = s->E; a.K = s->d_ffn; a.N = s->d_model;
+    a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
+    a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
+    a.gate_w = gate_w; a.top_k = s->top_k;
+    if (p.ksplit2 == 1) return launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, st);
+    a.partial = partial;
+    a.partial_rows = (long long)s->E * s->capacity;
+    int rc = launch_wsgemm(a, EPI_PARTIAL, p.MT, p.NW2, st);
+    if (rc != MOE_OK) return rc;
+    SplitKReduceArgs r{};
+    r.partial = partial; r.ksplit = p.ksplit2; r.G = s->E; r.N = s->d_model; r.group_stride = s->capacity;
+    r.rows = rows; r.max_rows = s->capacity; r.bias = u16(b2); r.out = u16(dst);
+    r.scatter_map = scatter ? slot_token : nullptr; r.gate_w = gate_w; r.top_k = s->top_k;
+    r.zero_slot_idx = scatter ? slot_idx : nullptr; r.T = s->T;
+    return launch_splitk_reduce(r, st);
+}
+
+// Dense branch of Residual-MoE on the MFMA kernel, with the combine fused into its second GEMM:
+// out[t, :] = gelu_tanh(x[t] Wd1 + bd1) Wd2 + bd2 + sum_j keep_j g_j ye[e_j, slot_j, :].
+int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const void* bd1, const void* Wd2,
+                     const void* bd2, void* hd, const void* ye, const int32_t* expert_idx, const int32_t* slot_idx,
+                     const float* gate_w, void* out, hipStream_t st) {
+    int MT, NW;
+    WsGemmArgs a{};
+    a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
+    a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
+    wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
+    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, st);
+    if (rc != MOE_OK) return rc;
+    a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
+    a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
+    a.C = s->capacity;
+    wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
+    return launch_wsgemm(a, EPI_COMBINE, MT, NW, st);
 }
 
 }  // namespace
@@ -141,8 +229,15 @@ int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expe
     rc = check_ws(shape, ws, ws_bytes);
     if (rc != MOE_OK) return rc;
     const WsLayout L = ws_layout(shape);
-    return run_ffn(shape->dtype, shape->E, shape->capacity, expert_rows, 0, shape->d_model, shape->d_ffn, xe, W1, b1,
-                   W2, b2, at<void>(ws, L.h), ye, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FfnPlan plan = plan_ffn(shape);
+    if (!plan.mfma)
+        return run_ffn_simple(shape->dtype, shape->E, shape->capacity, expert_rows, 0, shape->d_model, shape->d_ffn, xe,
+                              W1, b1, W2, b2, at<void>(ws, L.h), ye, st);
+    rc = run_expert_gemm1(shape, plan, xe, nullptr, expert_rows, W1, b1, at<void>(ws, L.h), st);
+    if (rc != MOE_OK) return rc;
+    return run_expert_gemm2(shape, plan, at<void>(ws, L.h), expert_rows, W2, b2, false, nullptr, nullptr, nullptr, ye,
+                            at<float>(ws, L.partial), st);
 }
 
 int moe_combine(const moe_shape_t* shape, const void* ye, const int32_t* expert_idx, const int32_t* slot_idx,
@@ -190,17 +285,38 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     if (rc != MOE_OK) return rc;
     rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, at<int32_t>(ws, L.hist), st);
     if (rc != MOE_OK) return rc;
-    rc = launch_dispatch(x, dt, slot_token, rows, at<void>(ws, L.xe), E, C, d, st);
-    if (rc != MOE_OK) return rc;
-    rc = run_ffn(dt, E, C, rows, 0, d, f, at<void>(ws, L.xe), W1, b1, W2, b2, at<void>(ws, L.h), at<void>(ws, L.ye), st);
-    if (rc != MOE_OK) return rc;
-    const void* addend = nullptr;
-    if (shape->residual) {
-        rc = run_ffn(dt, 1, T, nullptr, T, d, f, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd), at<void>(ws, L.dense), st);
+    const FfnPlan plan = plan_ffn(shape);
+    if (!plan.mfma) {
+        // fp32 layer: the unfused sequence dispatch -> FFN -> [dense branch] -> combine
+        rc = launch_dispatch(x, dt, slot_token, rows, at<void>(ws, L.xe), E, C, d, st);
         if (rc != MOE_OK) return rc;
-        addend = at<void>(ws, L.dense);
+        rc = run_ffn_simple(dt, E, C, rows, 0, d, f, at<void>(ws, L.xe), W1, b1, W2, b2, at<void>(ws, L.h),
+                            at<void>(ws, L.ye), st);
+        if (rc != MOE_OK) return rc;
+        const void* addend = nullptr;
+        if (shape->residual) {
+            rc = run_ffn_simple(dt, 1, T, nullptr, T, d, f, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd),
+                                at<void>(ws, L.dense), st);
+            if (rc != MOE_OK) return rc;
+            addend = at<void>(ws, L.dense);
+        }
+        return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
     }
-    return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
+
+    // bf16: dispatch is fused into GEMM-1 (rows gathered through slot_token) ...
+    rc = run_expert_gemm1(shape, plan, x, slot_token, rows, W1, b1, at<void>(ws, L.h), st);
+    if (rc != MOE_OK) return rc;
+    // ... and, for top-1 Standard-MoE, combine into GEMM-2 (scale by the gate weight, write the token's row)
+    if (k == 1 && !shape->residual)
+        return run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, W2, b2, true, slot_token, slot_idx, gate_w, out,
+                                at<float>(ws, L.partial), st);
+    rc = run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, W2, b2, false, nullptr, nullptr, nullptr,
+                          at<void>(ws, L.ye), at<float>(ws, L.partial), st);
+    if (rc != MOE_OK) return rc;
+    if (shape->residual)
+        return run_dense_branch(shape, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd), at<void>(ws, L.ye), expert_idx,
+                                slot_idx, gate_w, out, st);
+    return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, nullptr, out, T, k, C, d, st);
 }
 
 }  // extern "C"

@@ -1,0 +1,372 @@
+// bf16 grouped GEMM for the expert FFNs on gfx950 matrix cores (paper Sec. 3.1:
+// every expert is an FFN; Sec. 5.1: at inference the time to read the parameters
+// from memory dominates).  One kernel template serves both products of the FFN,
+// the dense branch of Residual-MoE (Sec. 4.1.1) and, through its epilogues, the
+// two layout transforms of Sec. 5.4 fused into the GEMMs:
+//   * GEMM-1 may read its rows straight from the token matrix through the
+//     slot->token table (dispatch without a dispatch buffer);
+//   * GEMM-2 may scale by the gate probability and write straight to the
+//     token's output row (top-1 combine without an expert-output buffer), or
+//     add the gathered expert outputs to the dense branch.
+//
+// Design: weight-streaming.  With tens of rows per expert the arithmetic
+// intensity is ~rows flop/byte, far below the MI355X ridge, so the kernel is
+// organised around reading every weight byte exactly once at full HBM rate:
+//   * a wave owns 128 output columns and marches down K; weights go
+//     HBM -> registers with 16-byte loads (8 columns of one k-row per lane),
+//     never through LDS, several 32-row "super-fragments" in flight;
+//   * the MFMA B operand needs 8 consecutive k per lane, the loads deliver 8
+//     consecutive n: an 8x8 16-bit transpose in registers (v_perm_b32) turns
+//     eight loads into eight B fragments, whose columns are interleaved
+//     (fragment i holds columns 8c+i) -- harmless, the epilogue then finds 8
+//     consecutive columns per lane and stores 16 bytes;
+//   * the small activation tile (MT rows x K) is shared by the block's waves
+//     through LDS in double-buffered k-chunks, rows padded by 16 bytes so the
+//     16-lane A-fragment reads hit distinct banks;
+//   * v_mfma_f32_16x16x32_bf16, fp32 accumulation.
+// Work-groups are numbered so that all row tiles of one (expert, column tile)
+// run on the same XCD back to back and share the weights through that XCD's L2.
+#include "moe_internal.h"
+
+namespace moe {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kXcd = 8;             // L2 domains; consecutive work-group ids rotate over them
+constexpr int kSF = 32;             // k-rows per super-fragment (one 16x16x32 MFMA deep)
+constexpr int kWaveCols = 128;      // output columns per wave
+constexpr int kLdsTileElems = 8192; // MT * KC: bf16 elements of one LDS activation buffer
+
+__device__ __forceinline__ uint32_t dw(const uint4& v, int q) {
+    return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
+}
+
+template <int MT, int NW, int EPI, int NBUF>
+__global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
+    constexpr int NT = NW * 64;
+    constexpr int MSUB = MT / 16;
+    constexpr int KC = kLdsTileElems / MT;        // k-extent of one LDS chunk
+    constexpr int STRIDE = KC * 2 + 16;           // bytes per LDS row
+    constexpr int PIECES = MT * KC / 8;           // 16-byte pieces per chunk
+    constexpr int NP = PIECES / NT;               // pieces per thread
+    constexpr int SFC = KC / kSF;                 // super-fragments per chunk
+    static_assert(PIECES % NT == 0 && SFC >= 1 && SFC % NBUF == 0, "tile configuration");
+
+    __shared__ __attribute__((aligned(16))) char lds[2 * MT * STRIDE];
+    __shared__ long long arow_sh[MT];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c = lane & 15, kg = lane >> 4;
+
+    // ---- which tile ------------------------------------------------------------------
+    const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
+    const int m_tiles = (a.max_rows + MT - 1) / MT;
+    const int inner_n = m_tiles * a.ksplit;
+    const int units = a.G * n_tiles;
+    const int xcd = blockIdx.x % kXcd;
+    const int q = blockIdx.x / kXcd;
+    const int inner = q % inner_n;
+    const int u = (q / inner_n) * kXcd + xcd;
+
+    // Top-1 combine fused into GEMM-2 leaves rows of dropped tokens unwritten: zero them here,
+    // spread over all work-groups (a dropped token has no other writer).
+    if (EPI == EPI_SCATTER && a.zero_slot_idx) {
+        for (int t = blockIdx.x; t < a.T; t += gridDim.x) {
+            if (a.zero_slot_idx[t] < 0) {
+                uint4* o = reinterpret_cast<uint4*>(a.out + (size_t)t * a.N);
+                for (int i = tid; i < a.N / 8; i += NT) o[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+    if (u >= units) return;
+    const int g = u / n_tiles, nt = u % n_tiles;
+    const int mt = inner % m_tiles, ks = inner / m_tiles;
+    const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
+    const int m0 = mt * MT;
+    if (m0 >= rows) return;
+    const int nrows = min(MT, rows - m0);
+
+    // ---- k range of this split (whole chunks) --------------------------------------------
+    const int chunks_total = (a.K + KC - 1) / KC;
+    const int chunks_per = (chunks_total + a.ksplit - 1) / a.ksplit;
+    const int ch_beg = ks * chunks_per;
+    const int ch_end = min(ch_beg + chunks_per, chunks_total);
+    if (ch_beg >= ch_end && EPI != EPI_PARTIAL) return;
+
+    // ---- A rows of the tile ----------------------------------------------------------
+    if (tid < MT) {
+        const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
+        long long ar;
+        if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
+        else ar = (long long)g * a.a_group_stride + r;
+        arow_sh[tid] = ar;
+    }
+    __syncthreads();
+
+    // ---- per-lane weight pointer: 8 columns n_lane..n_lane+7 of rows k ------------------------
+    const int n_lane_raw = nt * (NW * kWaveCols) + w * kWaveCols + c * 8;
+    const bool col_ok = n_lane_raw < a.N;
+    const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
+    const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
+
+    f32x4_t acc[MSUB][8];
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // activation chunk: global -> registers -> LDS
+    uint4 areg[NP];
+    auto a_load = [&](int ch) {
+        const int k0 = ch * KC;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int p = tid + i * NT;
+            const int r = p / (KC / 8), kp = p % (KC / 8);
+            const int k = k0 + kp * 8;
+            areg[i] = (k < a.K) ? *reinterpret_cast<const uint4*>(a.A + (size_t)arow_sh[r] * a.K + k)
+                                : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto a_store = [&](int buf) {
+        char* base = lds + buf * MT * STRIDE;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int p = tid + i * NT;
+            const int r = p / (KC / 8), kp = p % (KC / 8);
+            *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) = areg[i];
+        }
+    };
+
+    // weight super-fragment: rows k0 + kg*8 + j, j = 0..7 (clamped to the last row; A is zero there)
+    uint4 raw[NBUF][8];
+    auto b_load = [&](uint4 (&dst)[8], int k0) {
+        // K is a multiple of 8: a lane's 8 rows are all inside or all outside; outside ones re-read
+        // the last 8 rows (in bounds) and meet zeros on the activation side
+        const uint16_t* p = Bg + (size_t)min(k0 + kg * 8, a.K - 8) * a.N;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dst[j] = *reinterpret_cast<const uint4*>(p + (size_t)j * a.N);
+    };
+    auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
+        bf16x8_t af[MSUB];
+#pragma unroll
+        for (int ms = 0; ms < MSUB; ++ms)
+            af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t r0 = dw(src[2 * p], qq), r1 = dw(src[2 * p + 1], qq);
+                lo[p] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);   // column 2qq   : k = 2p, 2p+1
+                hi[p] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // column 2qq+1
+            }
+            const bf16x8_t blo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+            const bf16x8_t bhi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+#pragma unroll
+            for (int ms = 0; ms < MSUB; ++ms) {
+                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
+                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
+            }
+        }
+    };
+
+    if (ch_beg < ch_end) {
+        // prologue: first weight super-fragments in flight, first activation chunk in LDS
+#pragma unroll
+        for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
+        a_load(ch_beg);
+        a_store(0);
+        __syncthreads();
+
+        const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
+        const int k_last = ch_end * KC;       // first k-row beyond this split (weights are clamped)
+        for (int ch = ch_beg; ch < ch_end; ++ch) {
+            const int buf = (ch - ch_beg) & 1;
+            const bool more = ch + 1 < ch_end;
+            if (more) a_load(ch + 1);
+            const char* a_lane = a_lane0 + buf * MT * STRIDE;
+            const int kbase = ch * KC;
+#pragma unroll
+            for (int s = 0; s < SFC; s += NBUF) {
+#pragma unroll
+                for (int b = 0; b < NBUF; ++b) {
+                    // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b
+                    const int kpre = kbase + (s + b + NBUF - 1) * kSF;
+                    if (kpre < k_last) b_load(raw[(b + NBUF - 1) % NBUF], kpre);
+                    sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
+                }
+            }
+            if (more) a_store(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------
+    if (!col_ok) return;
+    const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
+    float bias[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+    if (a.bias && EPI != EPI_PARTIAL) {
+        const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + n_lane);
+        bias[0] = __uint_as_float(bv.x << 16); bias[1] = __uint_as_float(bv.x & 0xffff0000u);
+        bias[2] = __uint_as_float(bv.y << 16); bias[3] = __uint_as_float(bv.y & 0xffff0000u);
+        bias[4] = __uint_as_float(bv.z << 16); bias[5] = __uint_as_float(bv.z & 0xffff0000u);
+        bias[6] = __uint_as_float(bv.w << 16); bias[7] = __uint_as_float(bv.w & 0xffff0000u);
+    }
+#pragma unroll
+    for (int ms = 0; ms < MSUB; ++ms) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int rl = ms * 16 + mg * 4 + r;
+            if (rl >= nrows) continue;
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
+            const long long grow = (long long)g * a.o_group_stride + m0 + rl;   // row in [G, o_group_stride]
+            if (EPI == EPI_PARTIAL) {
+                float* o = a.partial + ((size_t)ks * a.partial_rows + grow) * a.N + n_lane;
+                *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                continue;
+            }
+            size_t orow = (size_t)grow;
+            if (EPI == EPI_GELU) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = gelu_tanh(v[i]);
+            } else if (EPI == EPI_SCATTER) {
+                const int t = a.scatter_map[(size_t)g * a.scatter_stride + m0 + rl];   // token of this expert row
+                const float gw = a.gate_w[(size_t)t * a.top_k];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] *= gw;
+                orow = (size_t)t;
+            } else if (EPI == EPI_COMBINE) {
+                // dense branch + sum_j keep_j g_j ye[e_j, slot_j, :] for token grow
+                for (int j = 0; j < a.top_k; ++j) {
+                    const int s = a.slot_idx[grow * a.top_k + j];
+                    if (s < 0) continue;
+                    const int e = a.expert_idx[grow * a.top_k + j];
+                    const float gw = a.gate_w[grow * a.top_k + j];
+                    const uint4 yv = *reinterpret_cast<const uint4*>(a.ye + ((size_t)e * a.C + s) * a.N + n_lane);
+                    v[0] = fmaf(gw, __uint_as_float(yv.x << 16), v[0]); v[1] = fmaf(gw, __uint_as_float(yv.x & 0xffff0000u), v[1]);
+                    v[2] = fmaf(gw, __uint_as_float(yv.y << 16), v[2]); v[3] = fmaf(gw, __uint_as_float(yv.y & 0xffff0000u), v[3]);
+                    v[4] = fmaf(gw, __uint_as_float(yv.z << 16), v[4]); v[5] = fmaf(gw, __uint_as_float(yv.z & 0xffff0000u), v[5]);
+                    v[6] = fmaf(gw, __uint_as_float(yv.w << 16), v[6]); v[7] = fmaf(gw, __uint_as_float(yv.w & 0xffff0000u), v[7]);
+                }
+            }
+            uint4 o;
+            o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
+            o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+            *reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Split-K finish: out = epilogue( sum_s partial[s] + bias ), splits summed in index order so the
+// result does not depend on scheduling.  One wave per expert row.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const SplitKReduceArgs a) {
+    const int lane = threadIdx.x & 63;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long nwaves = (long long)gridDim.x * 4;
+    const long long total_rows = (long long)a.G * a.group_stride;
+    if (a.scatter_map && a.zero_slot_idx) {
+        for (long long t = wave; t < a.T; t += nwaves) {
+            if (a.zero_slot_idx[t] < 0) {
+                uint4* o = reinterpret_cast<uint4*>(a.out + (size_t)t * a.N);
+                for (int i = lane; i < a.N / 8; i += 64) o[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+    for (long long row = wave; row < total_rows; row += nwaves) {
+        const int g = (int)(row / a.group_stride), r = (int)(row % a.group_stride);
+        if (r >= min(a.rows[g], a.max_rows)) continue;
+        float gw = 1.f;
+        size_t orow = (size_t)row;
+        if (a.scatter_map) {
+            const int t = a.scatter_map[row];
+            gw = a.gate_w[(size_t)t * a.top_k];
+            orow = (size_t)t;
+        }
+        for (int i = lane; i < a.N / 8; i += 64) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = 0.f;
+            for (int s = 0; s < a.ksplit; ++s) {
+                const float* p = a.partial + ((size_t)s * total_rows + row) * a.N + (size_t)i * 8;
+                const float4 x0 = *reinterpret_cast<const float4*>(p), x1 = *reinterpret_cast<const float4*>(p + 4);
+                v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
+                v[4] += x1.x; v[5] += x1.y; v[6] += x1.z; v[7] += x1.w;
+            }
+            if (a.bias) {
+                const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + (size_t)i * 8);
+                v[0] += __uint_as_float(bv.x << 16); v[1] += __uint_as_float(bv.x & 0xffff0000u);
+                v[2] += __uint_as_float(bv.y << 16); v[3] += __uint_as_float(bv.y & 0xffff0000u);
+                v[4] += __uint_as_float(bv.z << 16); v[5] += __uint_as_float(bv.z & 0xffff0000u);
+                v[6] += __uint_as_float(bv.w << 16); v[7] += __uint_as_float(bv.w & 0xffff0000u);
+            }
+            uint4 o;
+            o.x = pack_bf16x2(gw * v[0], gw * v[1]); o.y = pack_bf16x2(gw * v[2], gw * v[3]);
+            o.z = pack_bf16x2(gw * v[4], gw * v[5]); o.w = pack_bf16x2(gw * v[6], gw * v[7]);
+            *reinterpret_cast<uint4*>(a.out + orow * a.N + (size_t)i * 8) = o;
+        }
+    }
+}
+
+int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s) {
+    const long long total_rows = (long long)a.G * a.group_stride;
+    long long blocks = (total_rows + 3) / 4;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// ------------------------------------------------------------------------------------------
+template <int MT, int NW, int EPI>
+static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
+    constexpr int NBUF = 2;
+    const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
+    const int m_tiles = (a.max_rows + MT - 1) / MT;
+    const long long units = (long long)a.G * n_tiles;
+    const long long blocks = (units + kXcd - 1) / kXcd * kXcd * m_tiles * a.ksplit;
+    hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a);
+}
+
+template <int EPI>
+static void launch_epi(const WsGemmArgs& a, int MT, int NW, hipStream_t s) {
+#define MOE_WS_CASE(mt, nw) if (MT == mt && NW == nw) { launch_cfg<mt, nw, EPI>(a, s); return; }
+    MOE_WS_CASE(16, 4) MOE_WS_CASE(16, 2) MOE_WS_CASE(32, 4) MOE_WS_CASE(32, 2)
+    MOE_WS_CASE(64, 4) MOE_WS_CASE(64, 2)
+#undef MOE_WS_CASE
+}
+
+bool wsgemm_supported(int K, int N) { return K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
+
+void wsgemm_pick_tile(int max_rows, int G, int N, int* MT, int* NW) {
+    *MT = max_rows <= 16 ? 16 : max_rows <= 32 ? 32 : 64;
+    // enough work-groups to put two on every CU, otherwise narrower ones
+    const long long m_tiles = (max_rows + *MT - 1) / *MT;
+    const long long blocks4 = (long long)G * ((N + 4 * kWaveCols - 1) / (4 * kWaveCols)) * m_tiles;
+    *NW = blocks4 >= 512 ? 4 : 2;
+}
+
+int wsgemm_chunk_k(int MT) { return kLdsTileElems / MT; }
+
+int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, hipStream_t s) {
+    if (a.G <= 0 || a.max_rows <= 0) return MOE_OK;
+    if (a.ksplit < 1 || (a.ksplit > 1 && epi != EPI_PARTIAL)) return MOE_ERR_INVALID_ARG;
+    switch (epi) {
+        case EPI_STORE: launch_epi<EPI_STORE>(a, MT, NW, s); break;
+        case EPI_GELU: launch_epi<EPI_GELU>(a, MT, NW, s); break;
+        case EPI_SCATTER: launch_epi<EPI_SCATTER>(a, MT, NW, s); break;
+        case EPI_COMBINE: launch_epi<EPI_COMBINE>(a, MT, NW, s); break;
+        case EPI_PARTIAL: launch_epi<EPI_PARTIAL>(a, MT, NW, s); break;
+        default: return MOE_ERR_INVALID_ARG;
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+}  // namespace moe

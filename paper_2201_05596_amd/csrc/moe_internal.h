@@ -84,4 +84,62 @@ struct GemmArgs {
 };
 int launch_gemm_simple(const GemmArgs& a, hipStream_t s);
 
+// bf16 MFMA weight-streaming grouped GEMM (ffn_mfma.hip).
+enum WsEpilogue {
+    EPI_STORE = 0,    // out[g*o_group_stride + r, :] = acc + bias
+    EPI_GELU = 1,     // out[g*o_group_stride + r, :] = gelu_tanh(acc + bias)
+    EPI_SCATTER = 2,  // out[token(g,r), :] = gate_w[token, 0] * (acc + bias)        (top-1 combine)
+    EPI_COMBINE = 3,  // out[r, :] = acc + bias + sum_j keep_j g_j ye[e_j, slot_j, :]   (dense branch + combine)
+    EPI_PARTIAL = 4   // partial[ks, g*o_group_stride + r, :] = acc   (split-K, fp32, no bias)
+};
+struct WsGemmArgs {
+    const uint16_t* A;         // activations, leading dimension K
+    const uint16_t* B;         // [G, K, N]
+    const uint16_t* bias;      // [G, N] or nullptr
+    const int32_t* rows;       // [G] device row counts or nullptr -> fixed_rows
+    const int32_t* row_map;    // [G, map_stride]: A-row of (g, r), or nullptr -> g*a_group_stride + r
+    int32_t fixed_rows, max_rows, map_stride;
+    int32_t G, K, N;
+    long long a_group_stride;
+    uint16_t* out;             // leading dimension N
+    long long o_group_stride;
+    int32_t ksplit;            // >= 1; > 1 only with EPI_PARTIAL
+    float* partial;            // [ksplit, partial_rows, N]
+    long long partial_rows;
+    // EPI_SCATTER
+    const int32_t* scatter_map;    // [G, scatter_stride] token per expert row
+    int32_t scatter_stride;
+    const int32_t* zero_slot_idx;  // [T*top_k]: rows t with zero_slot_idx[t*top_k] < 0 are zero-filled (top_k == 1)
+    int32_t T;
+    // EPI_SCATTER / EPI_COMBINE
+    const float* gate_w;           // [T, top_k]
+    int32_t top_k;
+    const uint16_t* ye;            // [E, C, N]
+    const int32_t* expert_idx;     // [T, top_k]
+    const int32_t* slot_idx;       // [T, top_k]
+    int32_t C;
+};
+bool wsgemm_supported(int K, int N);
+void wsgemm_pick_tile(int max_rows, int G, int N, int* MT, int* NW);
+int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, hipStream_t s);
+int wsgemm_chunk_k(int MT);   // k-extent of one LDS chunk = granularity of split-K
+
+// Sums split-K partials in split order, adds the bias and finishes like EPI_STORE (scatter_map ==
+// nullptr) or EPI_SCATTER (scatter_map given; also zero-fills rows of dropped tokens).
+struct SplitKReduceArgs {
+    const float* partial;      // [ksplit, G*group_stride, N]
+    int32_t ksplit, G, N;
+    long long group_stride;
+    const int32_t* rows;       // [G]
+    int32_t max_rows;
+    const uint16_t* bias;      // [G, N] or nullptr
+    uint16_t* out;
+    const int32_t* scatter_map;
+    const float* gate_w;
+    int32_t top_k;
+    const int32_t* zero_slot_idx;
+    int32_t T;
+};
+int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s);
+
 }  // namespace moe
