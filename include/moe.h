@@ -140,6 +140,21 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
                       float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* Stage timing of moe_layer_forward, for benchmarks (the paper reports the MoE
+ * kernels' latency as a whole, Sec. 5.4; this splits it per kernel).
+ * moe_profile_enable(n > 0) creates events for the next n calls (the one place
+ * where the library creates a HIP resource), n = 0 disables and destroys them.
+ * While enabled, each moe_layer_forward call records one event on its stream
+ * before its first kernel and one after every stage; nothing is read back.
+ * moe_profile_elapsed(call, ms) waits for that call's last event and fills
+ * ms[moe_profile_stage_count()] with the milliseconds per stage (0 for stages
+ * the call did not run).  Not thread-safe. */
+int moe_profile_enable(int max_calls);
+int moe_profile_calls(void);
+int moe_profile_stage_count(void);
+const char* moe_profile_stage_name(int stage);
+int moe_profile_elapsed(int call, float* ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_dispatch",
-                "moe_expert_ffn", "moe_combine", "moe_layer_forward")
+                "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_calls",
+                "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
 
 
 class MoeShape(ctypes.Structure):
@@ -64,6 +65,16 @@ def load_library() -> ctypes.CDLL:
     lib.moe_combine.argtypes = [sp] + [vp] * 6 + [vp]
     lib.moe_layer_forward.restype = i32
     lib.moe_layer_forward.argtypes = [sp] + [vp] * 18 + [vp, st, vp]
+    lib.moe_profile_enable.restype = i32
+    lib.moe_profile_enable.argtypes = [i32]
+    lib.moe_profile_calls.restype = i32
+    lib.moe_profile_calls.argtypes = []
+    lib.moe_profile_stage_count.restype = i32
+    lib.moe_profile_stage_count.argtypes = []
+    lib.moe_profile_stage_name.restype = ctypes.c_char_p
+    lib.moe_profile_stage_name.argtypes = [i32]
+    lib.moe_profile_elapsed.restype = i32
+    lib.moe_profile_elapsed.argtypes = [i32, ctypes.POINTER(ctypes.c_float)]
     _lib = lib
     return lib
 
@@ -159,3 +170,24 @@ def moe_layer_forward(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out,
         _ptr(expert_rows_out, i32), _ptr(slot_token_out, i32),
         _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check("moe_layer_forward", rc)
+
+
+def moe_profile_enable(max_calls: int) -> None:
+    _check("moe_profile_enable", load_library().moe_profile_enable(int(max_calls)))
+
+
+def moe_profile_calls() -> int:
+    return int(load_library().moe_profile_calls())
+
+
+def moe_profile_stage_names() -> list:
+    lib = load_library()
+    return [lib.moe_profile_stage_name(i).decode() for i in range(lib.moe_profile_stage_count())]
+
+
+def moe_profile_elapsed(call: int) -> list:
+    lib = load_library()
+    n = lib.moe_profile_stage_count()
+    buf = (ctypes.c_float * n)()
+    _check("moe_profile_elapsed", lib.moe_profile_elapsed(int(call), buf))
+    return list(buf)

@@ -1,10 +1,41 @@
 // C ABI of the library: argument checks, workspace carving and launch sequencing.
 // Every check happens on the host before the first HIP call.
+#include <vector>
+
 #include "moe_internal.h"
 
 using namespace moe;
 
 namespace {
+
+// ---- optional stage timing of moe_layer_forward (benchmark aid) ----------------------------------
+// When enabled, an event is recorded on the call's stream before the first kernel and after every
+// stage; nothing is read back until moe_profile_elapsed() is called.
+enum Stage { ST_LOGITS, ST_ROUTE, ST_DISPATCH, ST_GEMM1, ST_GEMM2, ST_REDUCE, ST_DENSE1, ST_DENSE2, ST_COMBINE, ST_COUNT };
+const char* const kStageNames[ST_COUNT] = {"gate_logits", "gate_route", "dispatch", "expert_gemm1", "expert_gemm2",
+                                           "splitk_reduce", "dense_gemm1", "dense_gemm2", "combine"};
+struct Profiler {
+    int max_calls = 0, calls = 0, cur = -1;
+    std::vector<hipEvent_t> ev;     // [max_calls][ST_COUNT + 1]
+    std::vector<int> stage;         // stage that ended at each mark (mark 0 = start of the call)
+    std::vector<int> nmarks;        // [max_calls]
+} g_prof;
+
+void prof_begin(hipStream_t st) {
+    g_prof.cur = -1;
+    if (g_prof.max_calls == 0 || g_prof.calls >= g_prof.max_calls) return;
+    g_prof.cur = g_prof.calls++;
+    g_prof.nmarks[g_prof.cur] = 1;
+    (void)hipEventRecord(g_prof.ev[(size_t)g_prof.cur * (ST_COUNT + 1)], st);
+}
+void prof_mark(int stage, hipStream_t st) {
+    if (g_prof.cur < 0) return;
+    const int m = g_prof.nmarks[g_prof.cur];
+    if (m > ST_COUNT) return;
+    g_prof.stage[(size_t)g_prof.cur * (ST_COUNT + 1) + m] = stage;
+    (void)hipEventRecord(g_prof.ev[(size_t)g_prof.cur * (ST_COUNT + 1) + m], st);
+    g_prof.nmarks[g_prof.cur] = m + 1;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -115,7 +146,9 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
-    return launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, st);
+    const int rc = launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, st);
+    prof_mark(ST_GEMM1, st);
+    return rc;
 }
 
 // Expert GEMM-2 on the MFMA kernel.  scatter == false: ye[e, r, :] = h[e, r, :] W2[e] + b2[e].
@@ -129,17 +162,24 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
-    if (p.ksplit2 == 1) return launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, st);
+    if (p.ksplit2 == 1) {
+        const int rc1 = launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, st);
+        prof_mark(ST_GEMM2, st);
+        return rc1;
+    }
     a.partial = partial;
     a.partial_rows = (long long)s->E * s->capacity;
     int rc = launch_wsgemm(a, EPI_PARTIAL, p.MT, p.NW2, st);
+    prof_mark(ST_GEMM2, st);
     if (rc != MOE_OK) return rc;
     SplitKReduceArgs r{};
     r.partial = partial; r.ksplit = p.ksplit2; r.G = s->E; r.N = s->d_model; r.group_stride = s->capacity;
     r.rows = rows; r.max_rows = s->capacity; r.bias = u16(b2); r.out = u16(dst);
     r.scatter_map = scatter ? slot_token : nullptr; r.gate_w = gate_w; r.top_k = s->top_k;
     r.zero_slot_idx = scatter ? slot_idx : nullptr; r.T = s->T;
-    return launch_splitk_reduce(r, st);
+    rc = launch_splitk_reduce(r, st);
+    prof_mark(ST_REDUCE, st);
+    return rc;
 }
 
 // Dense branch of Residual-MoE on the MFMA kernel, with the combine fused into its second GEMM:
@@ -153,12 +193,15 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
     int rc = launch_wsgemm(a, EPI_GELU, MT, NW, st);
+    prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
     a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
     a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
-    return launch_wsgemm(a, EPI_COMBINE, MT, NW, st);
+    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, st);
+    prof_mark(ST_DENSE2, st);
+    return rc;
 }
 
 }  // namespace
@@ -281,26 +324,34 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     int32_t* rows = expert_rows_out ? expert_rows_out : at<int32_t>(ws, L.rows);
     int32_t* slot_token = slot_token_out ? slot_token_out : at<int32_t>(ws, L.slot_token);
 
+    prof_begin(st);
     rc = launch_gate_logits(x, dt, Wg, bg, logits, T, d, E, st);
+    prof_mark(ST_LOGITS, st);
     if (rc != MOE_OK) return rc;
     rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, at<int32_t>(ws, L.hist), st);
+    prof_mark(ST_ROUTE, st);
     if (rc != MOE_OK) return rc;
     const FfnPlan plan = plan_ffn(shape);
     if (!plan.mfma) {
         // fp32 layer: the unfused sequence dispatch -> FFN -> [dense branch] -> combine
         rc = launch_dispatch(x, dt, slot_token, rows, at<void>(ws, L.xe), E, C, d, st);
+        prof_mark(ST_DISPATCH, st);
         if (rc != MOE_OK) return rc;
         rc = run_ffn_simple(dt, E, C, rows, 0, d, f, at<void>(ws, L.xe), W1, b1, W2, b2, at<void>(ws, L.h),
                             at<void>(ws, L.ye), st);
+        prof_mark(ST_GEMM2, st);
         if (rc != MOE_OK) return rc;
         const void* addend = nullptr;
         if (shape->residual) {
             rc = run_ffn_simple(dt, 1, T, nullptr, T, d, f, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd),
                                 at<void>(ws, L.dense), st);
+            prof_mark(ST_DENSE2, st);
             if (rc != MOE_OK) return rc;
             addend = at<void>(ws, L.dense);
         }
-        return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
+        rc = launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
+        prof_mark(ST_COMBINE, st);
+        return rc;
     }
 
     // bf16: dispatch is fused into GEMM-1 (rows gathered through slot_token) ...
@@ -316,7 +367,44 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     if (shape->residual)
         return run_dense_branch(shape, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd), at<void>(ws, L.ye), expert_idx,
                                 slot_idx, gate_w, out, st);
-    return launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, nullptr, out, T, k, C, d, st);
+    rc = launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, nullptr, out, T, k, C, d, st);
+    prof_mark(ST_COMBINE, st);
+    return rc;
+}
+
+int moe_profile_enable(int max_calls) {
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof.ev.clear(); g_prof.stage.clear(); g_prof.nmarks.clear();
+    g_prof.max_calls = 0; g_prof.calls = 0; g_prof.cur = -1;
+    if (max_calls <= 0) return MOE_OK;
+    if (max_calls > 4096) return MOE_ERR_INVALID_ARG;
+    const size_t n = (size_t)max_calls * (ST_COUNT + 1);
+    g_prof.ev.resize(n);
+    for (size_t i = 0; i < n; ++i)
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) { g_prof.ev.resize(i); moe_profile_enable(0); return MOE_ERR_HIP; }
+    g_prof.stage.assign(n, -1);
+    g_prof.nmarks.assign(max_calls, 0);
+    g_prof.max_calls = max_calls;
+    return MOE_OK;
+}
+
+int moe_profile_calls(void) { return g_prof.calls; }
+int moe_profile_stage_count(void) { return ST_COUNT; }
+const char* moe_profile_stage_name(int i) { return (i >= 0 && i < ST_COUNT) ? kStageNames[i] : ""; }
+
+int moe_profile_elapsed(int call, float* ms) {
+    if (!ms || call < 0 || call >= g_prof.calls) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < ST_COUNT; ++i) ms[i] = 0.f;
+    const size_t base = (size_t)call * (ST_COUNT + 1);
+    const int m = g_prof.nmarks[call];
+    if (m < 2) return MOE_OK;
+    if (hipEventSynchronize(g_prof.ev[base + m - 1]) != hipSuccess) return MOE_ERR_HIP;
+    for (int i = 1; i < m; ++i) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, g_prof.ev[base + i - 1], g_prof.ev[base + i]) != hipSuccess) return MOE_ERR_HIP;
+        ms[g_prof.stage[base + i]] += t;
+    }
+    return MOE_OK;
 }
 
 }  // extern "C"

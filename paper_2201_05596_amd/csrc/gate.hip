@@ -13,66 +13,148 @@
 namespace moe {
 
 // ------------------------------------------------------------------------------------------
-// logits[t,e] = bg[e] + sum_i x[t,i] Wg[i,e]     fp32 accumulate
+// logits[t,e] = bg[e] + sum_i x[t,i] Wg[i,e]     fp32 in, fp32 accumulate, on the fp32 matrix cores
 //
-// Block = 256 threads = EB expert lanes x (256/EB) token groups, 8 tokens per
-// thread.  The x tile is staged in LDS as fp32 and read back as broadcast
-// 16-byte vectors; Wg rows are read coalesced straight from L2.
+// v_mfma_f32_16x16x4_f32: a wave owns 16 tokens x 64 experts (4 accumulator tiles).  Per 32-wide
+// k-chunk a lane reads 8 consecutive k of its token row straight from global memory (16 bytes of
+// bf16, widened by a shift, or 32 bytes of fp32) and feeds them to 8 successive MFMAs; lane group
+// g = lane/16 therefore holds k = 8g + j in MFMA j, and reads the matching Wg row 8g + j from an
+// LDS tile kept in Wg's own [k][e] layout (columns rotated by 16 per 8 rows so that the four lane
+// groups hit different banks).  No transposition anywhere.  A work-group is WT x WE x WK waves:
+// token tiles x 64-expert tiles x k-splits (the k-split, summed through LDS in fixed order, keeps
+// every CU busy when there are few tokens).
 // ------------------------------------------------------------------------------------------
-constexpr int kLogitKC = 64;     // k-chunk of the x tile
-constexpr int kLogitTPT = 8;     // tokens per thread
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kGK = 32;      // k-chunk
 
-template <typename XT, int EB>
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(a.x << 16); v[1] = __uint_as_float(a.x & 0xffff0000u);
+    v[2] = __uint_as_float(a.y << 16); v[3] = __uint_as_float(a.y & 0xffff0000u);
+    v[4] = __uint_as_float(a.z << 16); v[5] = __uint_as_float(a.z & 0xffff0000u);
+    v[6] = __uint_as_float(a.w << 16); v[7] = __uint_as_float(a.w & 0xffff0000u);
+}
+// 4 consecutive k (fp32 rows whose length is a multiple of 4 but not of 8)
+__device__ __forceinline__ void load4(const float* p, float* v) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+}
+
+template <typename XT, int WT, int WE, int WK>
 __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__ x, const float* __restrict__ Wg,
                                                           const float* __restrict__ bg, float* __restrict__ logits,
                                                           int T, int d, int E) {
-    constexpr int NTH = 256 / EB;
-    constexpr int TM = NTH * kLogitTPT;
-    __shared__ __attribute__((aligned(16))) float xs[TM][kLogitKC + 4];
+    static_assert(WT * WE * WK == 4, "four waves");
+    constexpr int EN = WE * 64;                 // experts per pass of the work-group
+    constexpr int TM = WT * 16;                 // tokens per work-group
+    constexpr int NB = WK * kGK * EN / 256;     // Wg elements staged per thread and pass
+    __shared__ __attribute__((aligned(16))) float Bs[WK][kGK][EN];
+    __shared__ float red[WK > 1 ? (WK - 1) * WT * WE * 16 * 64 : 1];
 
-    const int tid = threadIdx.x;
-    const int el = tid % EB;
-    const int th = tid / EB;
-    const int t0 = blockIdx.x * TM;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int wk = w % WK, we = (w / WK) % WE, wt = w / (WK * WE);
+    const int t0 = blockIdx.x * TM + wt * 16;
+    const int trow = min(t0 + n, T - 1);                            // A row of this lane (clamped, not stored)
+    const XT* xrow = x + (size_t)trow * d;
 
-    for (int e0 = 0; e0 < E; e0 += EB) {
-        const int e = e0 + el;
-        const bool e_ok = e < E;
-        float acc[kLogitTPT];
+    // k is cut into 32-wide chunks; split s of the WK k-splits owns chunks [s*cper, (s+1)*cper).
+    // In pass c the work-group stages chunk s*cper + c of every split, and each wave multiplies
+    // its own split's tile.
+    const int chunks = (d + kGK - 1) / kGK;
+    const int cper = (chunks + WK - 1) / WK;
+
+    for (int e0 = 0; e0 < E; e0 += EN) {
+        f32x4_t acc[4];
 #pragma unroll
-        for (int i = 0; i < kLogitTPT; ++i) acc[i] = 0.f;
+        for (int i = 0; i < 4; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        for (int k0 = 0; k0 < d; k0 += kLogitKC) {
-            __syncthreads();
-            for (int i = tid; i < TM * kLogitKC; i += 256) {
-                const int r = i / kLogitKC, c = i % kLogitKC;
-                const int t = t0 + r, k = k0 + c;
-                xs[r][c] = (t < T && k < d) ? Elem<XT>::load(x + (size_t)t * d + k) : 0.f;
+        float breg[NB];
+        auto b_load = [&](int c) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int p = tid + i * 256;
+                const int s = p / (kGK * EN), kk = (p / EN) % kGK, ee = p % EN;
+                const int ch = s * cper + c;
+                const int k = ch * kGK + kk, e = e0 + ee;
+                breg[i] = (c < cper && k < d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
             }
+        };
+        auto b_store = [&]() {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int p = tid + i * 256;
+                const int s = p / (kGK * EN), kk = (p / EN) % kGK, ee = p % EN;
+                Bs[s][kk][(ee + 16 * (kk >> 3)) % EN] = breg[i];
+            }
+        };
+        auto a_load = [&](int c, float (&v)[8]) {
+            const int k = (wk * cper + c) * kGK + 8 * g;
+            if (c < cper && k + 8 <= d) {
+                load8(xrow + k, v);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = 0.f;
+                if (sizeof(XT) == 4 && c < cper && k + 4 <= d) load4(reinterpret_cast<const float*>(xrow) + k, v);
+            }
+        };
+
+        float av[8], av_next[8];
+        b_load(0);
+        a_load(0, av_next);
+        for (int c = 0; c < cper; ++c) {
+            __syncthreads();                 // the previous pass has finished reading the tile
+            b_store();
             __syncthreads();
-            const int kmax = min(kLogitKC, d - k0);
-            if (e_ok) {
-                for (int kk = 0; kk < kmax; kk += 4) {
-                    float w[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) w[i] = (kk + i < kmax) ? Wg[(size_t)(k0 + kk + i) * E + e] : 0.f;
+            for (int j = 0; j < 8; ++j) av[j] = av_next[j];
+            b_load(c + 1);                   // prefetch the next pass while this one is multiplied
+            a_load(c + 1, av_next);
 #pragma unroll
-                    for (int tt = 0; tt < kLogitTPT; ++tt) {
-                        const float4 xv = *reinterpret_cast<const float4*>(&xs[th * kLogitTPT + tt][kk]);
-                        acc[tt] = fmaf(xv.x, w[0], acc[tt]);
-                        acc[tt] = fmaf(xv.y, w[1], acc[tt]);
-                        acc[tt] = fmaf(xv.z, w[2], acc[tt]);
-                        acc[tt] = fmaf(xv.w, w[3], acc[tt]);
-                    }
+            for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const float b = Bs[wk][8 * g + j][(we * 64 + nt * 16 + n + 16 * g) % EN];
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j], b, acc[nt], 0, 0, 0);
                 }
             }
         }
-        if (e_ok) {
-            const float b = bg ? bg[e] : 0.f;
+
+        if (WK > 1) {
+            __syncthreads();
+            float* mine = red + ((size_t)((wk - 1) * WT * WE + wt * WE + we) * 16) * 64;
+            if (wk > 0) {
 #pragma unroll
-            for (int tt = 0; tt < kLogitTPT; ++tt) {
-                const int t = t0 + th * kLogitTPT + tt;
-                if (t < T) logits[(size_t)t * E + e] = acc[tt] + b;
+                for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) mine[(nt * 4 + r) * 64 + lane] = acc[nt][r];
+            }
+            __syncthreads();
+            if (wk == 0) {
+                for (int s = 1; s < WK; ++s) {
+                    const float* o = red + ((size_t)((s - 1) * WT * WE + wt * WE + we) * 16) * 64;
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[nt][r] += o[(nt * 4 + r) * 64 + lane];
+                }
+            }
+        }
+        if (wk == 0) {
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const int e = e0 + we * 64 + nt * 16 + n;
+                if (e >= E) continue;
+                const float b = bg ? bg[e] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int t = t0 + 4 * g + r;
+                    if (t < T) logits[(size_t)t * E + e] = acc[nt][r] + b;
+                }
             }
         }
     }
@@ -81,17 +163,18 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__
 template <typename XT>
 static int launch_logits_t(const XT* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
                            hipStream_t s) {
-#define MOE_LOGITS_CASE(EB)                                                                           \
-    {                                                                                                 \
-        constexpr int TM = (256 / EB) * kLogitTPT;                                                    \
-        hipLaunchKernelGGL((gate_logits_kernel<XT, EB>), dim3((T + TM - 1) / TM), dim3(256), 0, s, x, \
-                           Wg, bg, logits, T, d, E);                                                  \
+#define MOE_LOGITS_CASE(WT, WE, WK)                                                                       \
+    hipLaunchKernelGGL((gate_logits_kernel<XT, WT, WE, WK>), dim3((T + WT * 16 - 1) / (WT * 16)), dim3(256), 0, \
+                       s, x, Wg, bg, logits, T, d, E)
+    const bool wide = E > 64;          // 128 experts per pass, else 64
+    const bool few = T <= 1024;        // few tokens: spend waves on k-splits instead of token tiles
+    if (wide) {
+        if (few) MOE_LOGITS_CASE(1, 2, 2);
+        else MOE_LOGITS_CASE(2, 2, 1);
+    } else {
+        if (few) MOE_LOGITS_CASE(1, 1, 4);
+        else MOE_LOGITS_CASE(4, 1, 1);
     }
-    if (E <= 16) MOE_LOGITS_CASE(16)
-    else if (E <= 32) MOE_LOGITS_CASE(32)
-    else if (E <= 64) MOE_LOGITS_CASE(64)
-    else if (E <= 128) MOE_LOGITS_CASE(128)
-    else MOE_LOGITS_CASE(256)
 #undef MOE_LOGITS_CASE
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -104,7 +187,7 @@ int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* b
 
 // ------------------------------------------------------------------------------------------
 // Routing, kernel 1 of 2: per block of 256 tokens
-//   phase A  one wave per token: top-k by logit (lowest index on ties), softmax weight(s)
+//   phase A  16 lanes per token: top-k by logit (lowest index on ties), softmax weight(s)
 //   phase B  one lane per token: rank of the token among the wave's tokens that chose the same
 //            expert, by ballot; per-wave histogram
 //   phase C  prefix over the block's waves; block histogram to global scratch; the rank inside
@@ -118,9 +201,10 @@ struct Best {
 __device__ __forceinline__ Best better(Best a, Best b) {
     return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
 }
-__device__ __forceinline__ Best wave_best(Best a) {
+// reductions inside aligned groups of 16 lanes (xor masks < 16 never leave the group)
+__device__ __forceinline__ Best group_best(Best a) {
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
+    for (int m = 8; m >= 1; m >>= 1) {
         Best o;
         o.v = __shfl_xor(a.v, m, kWave);
         o.i = __shfl_xor(a.i, m, kWave);
@@ -128,13 +212,62 @@ __device__ __forceinline__ Best wave_best(Best a) {
     }
     return a;
 }
-__device__ __forceinline__ float wave_sum(float a) {
+__device__ __forceinline__ float group_sum(float a) {
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) a += __shfl_xor(a, m, kWave);
+    for (int m = 8; m >= 1; m >>= 1) a += __shfl_xor(a, m, kWave);
     return a;
 }
 
-template <int K>
+// Top-K experts and gate weights of one token, computed by a group of 16 lanes; lane `sub` looks
+// at experts sub, sub+16, ...  NV > 0: the row fits NV registers per lane (E <= 16*NV), one pass.
+// NV == 0: any E, two passes over the row.  Every lane of the group returns the same result.
+template <int K, int NV>
+__device__ __forceinline__ void token_gate(const float* __restrict__ row, int E, int sub, Best& g1, Best& g2,
+                                           float& w1, float& w2) {
+    const Best none{-INFINITY, 0x7fffffff};
+    Best b1 = none, b2 = none;
+    float s = 0.f;
+    if (NV > 0) {
+        float v[NV > 0 ? NV : 1];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = sub + 16 * i;
+            v[i] = e < E ? row[e] : -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = sub + 16 * i;
+            if (v[i] > b1.v) { b2 = b1; b1.v = v[i]; b1.i = e; }
+            else if (v[i] > b2.v) { b2.v = v[i]; b2.i = e; }
+        }
+        g1 = group_best(b1);
+        g2 = none;
+        if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) s += expf(v[i] - g1.v);       // exp(-inf) = 0 for the padding
+    } else {
+        for (int e = sub; e < E; e += 16) {
+            const float v = row[e];
+            if (v > b1.v) { b2 = b1; b1.v = v; b1.i = e; }
+            else if (v > b2.v) { b2.v = v; b2.i = e; }
+        }
+        g1 = group_best(b1);
+        g2 = none;
+        if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
+        for (int e = sub; e < E; e += 16) s += expf(row[e] - g1.v);
+    }
+    s = group_sum(s);
+    if (K == 1) {
+        w1 = 1.0f / s;                       // softmax probability of the arg-max
+        w2 = 0.f;
+    } else {
+        const float r = expf(g2.v - g1.v);   // p2/p1; renormalised pair = (1, r)/(1 + r)
+        w1 = 1.0f / (1.0f + r);
+        w2 = r / (1.0f + r);
+    }
+}
+
+template <int K, int NV>
 __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* __restrict__ logits, int T, int E,
                                                                    int32_t* __restrict__ expert_idx,
                                                                    int32_t* __restrict__ slot_idx,
@@ -150,41 +283,29 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 
     for (int i = tid; i < NW * K * E; i += kRouteTokens) whist[i] = 0;
 
-    // phase A
-    for (int q = 0; q < kWave; ++q) {
-        const int tl = w * kWave + q;
-        const int t = tb + tl;
-        if (t >= T) {                                 // wave-uniform
-            if (lane == 0) {
-                e_sh[tl] = -1;
-                if (K == 2) e_sh[kRouteTokens + tl] = -1;
-            }
-            continue;
-        }
-        const float* row = logits + (size_t)t * E;
-        Best b1{-INFINITY, 0x7fffffff}, b2{-INFINITY, 0x7fffffff};
-        for (int e = lane; e < E; e += kWave) {
-            const float v = row[e];
-            if (v > b1.v) { b2 = b1; b1.v = v; b1.i = e; }
-            else if (v > b2.v) { b2.v = v; b2.i = e; }
-        }
-        const Best g1 = wave_best(b1);
-        Best g2{-INFINITY, 0x7fffffff};
-        if (K == 2) g2 = wave_best(b1.i == g1.i ? b2 : b1);
-        float s = 0.f;
-        for (int e = lane; e < E; e += kWave) s += expf(row[e] - g1.v);
-        s = wave_sum(s);
-        if (lane == 0) {
-            e_sh[tl] = g1.i;
-            expert_idx[(size_t)t * K] = g1.i;
-            if (K == 1) {
-                gate_w[t] = 1.0f / s;
-            } else {
-                const float r = expf(g2.v - g1.v);
-                e_sh[kRouteTokens + tl] = g2.i;
-                expert_idx[(size_t)t * K + 1] = g2.i;
-                gate_w[(size_t)t * K] = 1.0f / (1.0f + r);
-                gate_w[(size_t)t * K + 1] = r / (1.0f + r);
+    // phase A: 16 lanes per token, 16 tokens of the block at a time
+    {
+        const int grp = tid >> 4, sub = tid & 15;
+#pragma unroll 4
+        for (int it = 0; it < kRouteTokens / 16; ++it) {
+            const int tl = it * 16 + grp;
+            const int t = tb + tl;
+            const int tc = min(t, T - 1);                 // clamp: all lanes stay in the shuffles
+            Best g1, g2;
+            float w1, w2;
+            token_gate<K, NV>(logits + (size_t)tc * E, E, sub, g1, g2, w1, w2);
+            if (sub == 0) {
+                const bool ok = t < T;
+                e_sh[tl] = ok ? g1.i : -1;
+                if (K == 2) e_sh[kRouteTokens + tl] = ok ? g2.i : -1;
+                if (ok) {
+                    expert_idx[(size_t)t * K] = g1.i;
+                    gate_w[(size_t)t * K] = w1;
+                    if (K == 2) {
+                        expert_idx[(size_t)t * K + 1] = g2.i;
+                        gate_w[(size_t)t * K + 1] = w2;
+                    }
+                }
             }
         }
     }
@@ -251,16 +372,32 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
 
+    // column = (choice j, expert e); the blocks' histograms are summed with all 256 threads: R row
+    // groups each take every R-th block, partial sums meet in LDS
+    const int ncol = K * E;
+    int32_t* part = rows_sh + E;                           // [2][R][ncol]: before-me sums, all-blocks sums
+    const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
+    for (int idx = tid; idx < R * ncol; idx += kRouteTokens) {
+        const int col = idx % ncol, rg = idx / ncol;
+        int pre = 0, tot = 0;
+#pragma unroll 8
+        for (int bb = rg; bb < nblocks; bb += R) {
+            const int v = hist[(size_t)bb * ncol + col];
+            tot += v;
+            pre += bb < b ? v : 0;
+        }
+        part[rg * ncol + col] = pre;
+        part[(R + rg) * ncol + col] = tot;
+    }
+    __syncthreads();
     for (int e = tid; e < E; e += kRouteTokens) {
         int pre[K], tot[K];
 #pragma unroll
-        for (int j = 0; j < K; ++j) pre[j] = tot[j] = 0;
-        for (int bb = 0; bb < nblocks; ++bb) {
-#pragma unroll
-            for (int j = 0; j < K; ++j) {
-                const int v = hist[((size_t)bb * K + j) * E + e];
-                tot[j] += v;
-                if (bb < b) pre[j] += v;
+        for (int j = 0; j < K; ++j) {
+            pre[j] = tot[j] = 0;
+            for (int rg = 0; rg < R; ++rg) {
+                pre[j] += part[rg * ncol + j * E + e];
+                tot[j] += part[(R + rg) * ncol + j * E + e];
             }
         }
         base[e] = pre[0];
@@ -310,18 +447,30 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const int NW = kRouteTokens / kWave;
     const size_t sm1 = sizeof(int32_t) * ((size_t)k * kRouteTokens + (size_t)NW * k * E);
-    const size_t sm2 = sizeof(int32_t) * ((size_t)k * E + E);
+    const int ncol = k * E;
+    const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
+    const size_t sm2 = sizeof(int32_t) * ((size_t)k * E + E + 2 * (size_t)R * ncol);
+#define MOE_ROUTE_LOCAL(K, NV)                                                                                   \
+    hipLaunchKernelGGL((route_local_kernel<K, NV>), dim3(nb), dim3(kRouteTokens), sm1, s, logits, T, E, expert_idx, \
+                       slot_idx, gate_w, scratch)
     if (k == 1) {
-        hipLaunchKernelGGL((route_local_kernel<1>), dim3(nb), dim3(kRouteTokens), sm1, s, logits, T, E,
-                           expert_idx, slot_idx, gate_w, scratch);
+        if (E <= 16) MOE_ROUTE_LOCAL(1, 1);
+        else if (E <= 32) MOE_ROUTE_LOCAL(1, 2);
+        else if (E <= 64) MOE_ROUTE_LOCAL(1, 4);
+        else if (E <= 128) MOE_ROUTE_LOCAL(1, 8);
+        else MOE_ROUTE_LOCAL(1, 0);
         hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
                            expert_idx, slot_idx, expert_rows, slot_token, scratch);
     } else {
-        hipLaunchKernelGGL((route_local_kernel<2>), dim3(nb), dim3(kRouteTokens), sm1, s, logits, T, E,
-                           expert_idx, slot_idx, gate_w, scratch);
+        if (E <= 16) MOE_ROUTE_LOCAL(2, 1);
+        else if (E <= 32) MOE_ROUTE_LOCAL(2, 2);
+        else if (E <= 64) MOE_ROUTE_LOCAL(2, 4);
+        else if (E <= 128) MOE_ROUTE_LOCAL(2, 8);
+        else MOE_ROUTE_LOCAL(2, 0);
         hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
                            expert_idx, slot_idx, expert_rows, slot_token, scratch);
     }
+#undef MOE_ROUTE_LOCAL
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
