@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks, workspace carving and launch sequencing.
 // Every check happens on the host before the first HIP call.
+#include <cstdlib>
 #include <vector>
 
 #include "moe_internal.h"
@@ -62,16 +63,27 @@ struct FfnPlan {
     bool mfma;          // false: plain fp32-ALU GEMM (fp32 layers)
     int MT, NW1, NW2;   // row tile; waves per work-group of GEMM-1 / GEMM-2
     int ksplit2;        // split-K factor of GEMM-2 (1 = none)
+    int NBUF;           // weight super-fragments kept in flight per wave, plus one
 };
+
+// developer tuning knobs (environment), 0 = not set
+int tune(const char* name) {
+    const char* v = std::getenv(name);
+    return v ? std::atoi(v) : 0;
+}
 
 FfnPlan plan_ffn(const moe_shape_t* s) {
     FfnPlan p{};
     p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
     p.ksplit2 = 1;
+    p.NBUF = tune("MOE_TUNE_NBUF") ? tune("MOE_TUNE_NBUF") : 2;
     if (!p.mfma) return p;
     wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
     int mt2;
     wsgemm_pick_tile(s->capacity, s->E, s->d_model, &mt2, &p.NW2);
+    if (tune("MOE_TUNE_MT")) p.MT = tune("MOE_TUNE_MT");
+    if (tune("MOE_TUNE_NW1")) p.NW1 = tune("MOE_TUNE_NW1");
+    if (tune("MOE_TUNE_NW2")) p.NW2 = tune("MOE_TUNE_NW2");
     // GEMM-2 has few output columns; when that leaves the chip short of waves, split K
     const long long touched = s->E < (long long)s->T * s->top_k ? s->E : (long long)s->T * s->top_k;
     const long long m_tiles = (s->capacity + p.MT - 1) / p.MT;
@@ -82,6 +94,10 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
         if (ks > 8) ks = 8;
         if (ks > chunks) ks = chunks;
         p.ksplit2 = (int)(ks < 1 ? 1 : ks);
+    }
+    if (tune("MOE_TUNE_KSPLIT")) {
+        const int chunks = (s->d_ffn + wsgemm_chunk_k(p.MT) - 1) / wsgemm_chunk_k(p.MT);
+        p.ksplit2 = tune("MOE_TUNE_KSPLIT") < chunks ? tune("MOE_TUNE_KSPLIT") : chunks;
     }
     return p;
 }
@@ -146,7 +162,7 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
-    const int rc = launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, st);
+    const int rc = launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
     prof_mark(ST_GEMM1, st);
     return rc;
 }
@@ -163,13 +179,13 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
     if (p.ksplit2 == 1) {
-        const int rc1 = launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, st);
+        const int rc1 = launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, p.NBUF, st);
         prof_mark(ST_GEMM2, st);
         return rc1;
     }
     a.partial = partial;
     a.partial_rows = (long long)s->E * s->capacity;
-    int rc = launch_wsgemm(a, EPI_PARTIAL, p.MT, p.NW2, st);
+    int rc = launch_wsgemm(a, EPI_PARTIAL, p.MT, p.NW2, p.NBUF, st);
     prof_mark(ST_GEMM2, st);
     if (rc != MOE_OK) return rc;
     SplitKReduceArgs r{};
@@ -192,14 +208,14 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
-    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, st);
+    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, 2, st);
     prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
     a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
     a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
-    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, st);
+    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, 2, st);
     prof_mark(ST_DENSE2, st);
     return rc;
 }

@@ -116,26 +116,36 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // activation chunk: global -> registers -> LDS
+    // activation chunk: global -> registers -> LDS.  Each thread moves NP 16-byte pieces per chunk;
+    // their rows and k-offsets never change, so the row pointers are formed once.  The loads are
+    // unconditional (k clamped into the row, the value replaced by zero past K) so that the main
+    // loop has no branches around memory operations and the prefetches really stay in flight.
+    const uint16_t* arow_ptr[NP];
+    int akp[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int p = tid + i * NT;
+        arow_ptr[i] = a.A + (size_t)arow_sh[p / (KC / 8)] * a.K;
+        akp[i] = (p % (KC / 8)) * 8;
+    }
     uint4 areg[NP];
-    auto a_load = [&](int ch) {
+    auto a_load = [&](int ch) {                     // loads only: nothing here waits for them
+        const int k0 = ch * KC;
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+            areg[i] = *reinterpret_cast<const uint4*>(arow_ptr[i] + min(k0 + akp[i], a.K - 8));
+    };
+    auto a_store = [&](int ch, int buf) {           // zero past K, then registers -> LDS
+        char* base = lds + buf * MT * STRIDE;
         const int k0 = ch * KC;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int p = tid + i * NT;
             const int r = p / (KC / 8), kp = p % (KC / 8);
-            const int k = k0 + kp * 8;
-            areg[i] = (k < a.K) ? *reinterpret_cast<const uint4*>(a.A + (size_t)arow_sh[r] * a.K + k)
-                                : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto a_store = [&](int buf) {
-        char* base = lds + buf * MT * STRIDE;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int p = tid + i * NT;
-            const int r = p / (KC / 8), kp = p % (KC / 8);
-            *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) = areg[i];
+            const bool in = k0 + akp[i] < a.K;
+            const uint4 v = areg[i];
+            *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) =
+                make_uint4(in ? v.x : 0u, in ? v.y : 0u, in ? v.z : 0u, in ? v.w : 0u);
         }
     };
 
@@ -177,28 +187,31 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
 #pragma unroll
         for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
         a_load(ch_beg);
-        a_store(0);
+        a_store(ch_beg, 0);
         __syncthreads();
 
         const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
-        const int k_last = ch_end * KC;       // first k-row beyond this split (weights are clamped)
         for (int ch = ch_beg; ch < ch_end; ++ch) {
             const int buf = (ch - ch_beg) & 1;
-            const bool more = ch + 1 < ch_end;
-            if (more) a_load(ch + 1);
+            a_load(ch + 1);                    // next chunk (past the end: clamped and zeroed, never used)
+            __builtin_amdgcn_sched_barrier(0);
             const char* a_lane = a_lane0 + buf * MT * STRIDE;
             const int kbase = ch * KC;
 #pragma unroll
             for (int s = 0; s < SFC; s += NBUF) {
 #pragma unroll
                 for (int b = 0; b < NBUF; ++b) {
-                    // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b
-                    const int kpre = kbase + (s + b + NBUF - 1) * kSF;
-                    if (kpre < k_last) b_load(raw[(b + NBUF - 1) % NBUF], kpre);
+                    // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b.
+                    // Unconditional: past the last row the loads re-read the last rows and are dropped.
+                    // The scheduling barriers pin that order: left alone, the compiler sinks the loads
+                    // down to their first use and the prefetch distance collapses to zero.
+                    b_load(raw[(b + NBUF - 1) % NBUF], kbase + (s + b + NBUF - 1) * kSF);
+                    __builtin_amdgcn_sched_barrier(0);
                     sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (more) a_store(buf ^ 1);
+            a_store(ch + 1, buf ^ 1);
             __syncthreads();
         }
     }
@@ -325,9 +338,8 @@ int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
-template <int MT, int NW, int EPI>
+template <int MT, int NW, int EPI, int NBUF>
 static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
-    constexpr int NBUF = 2;
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
     const long long units = (long long)a.G * n_tiles;
@@ -336,11 +348,14 @@ static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
 }
 
 template <int EPI>
-static void launch_epi(const WsGemmArgs& a, int MT, int NW, hipStream_t s) {
-#define MOE_WS_CASE(mt, nw) if (MT == mt && NW == nw) { launch_cfg<mt, nw, EPI>(a, s); return; }
-    MOE_WS_CASE(16, 4) MOE_WS_CASE(16, 2) MOE_WS_CASE(32, 4) MOE_WS_CASE(32, 2)
-    MOE_WS_CASE(64, 4) MOE_WS_CASE(64, 2)
+static bool launch_epi(const WsGemmArgs& a, int MT, int NW, int NBUF, hipStream_t s) {
+#define MOE_WS_CASE(mt, nw, nb) if (MT == mt && NW == nw && NBUF == nb) { launch_cfg<mt, nw, EPI, nb>(a, s); return true; }
+    MOE_WS_CASE(16, 4, 2) MOE_WS_CASE(16, 2, 2) MOE_WS_CASE(32, 4, 2) MOE_WS_CASE(32, 2, 2)
+    MOE_WS_CASE(64, 4, 2) MOE_WS_CASE(64, 2, 2)
+    MOE_WS_CASE(16, 4, 4) MOE_WS_CASE(16, 2, 4) MOE_WS_CASE(32, 4, 4) MOE_WS_CASE(32, 2, 4)
+    MOE_WS_CASE(64, 4, 4) MOE_WS_CASE(64, 2, 4)
 #undef MOE_WS_CASE
+    return false;
 }
 
 bool wsgemm_supported(int K, int N) { return K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
@@ -355,17 +370,19 @@ void wsgemm_pick_tile(int max_rows, int G, int N, int* MT, int* NW) {
 
 int wsgemm_chunk_k(int MT) { return kLdsTileElems / MT; }
 
-int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, hipStream_t s) {
+int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, int NBUF, hipStream_t s) {
     if (a.G <= 0 || a.max_rows <= 0) return MOE_OK;
     if (a.ksplit < 1 || (a.ksplit > 1 && epi != EPI_PARTIAL)) return MOE_ERR_INVALID_ARG;
+    bool ok = false;
     switch (epi) {
-        case EPI_STORE: launch_epi<EPI_STORE>(a, MT, NW, s); break;
-        case EPI_GELU: launch_epi<EPI_GELU>(a, MT, NW, s); break;
-        case EPI_SCATTER: launch_epi<EPI_SCATTER>(a, MT, NW, s); break;
-        case EPI_COMBINE: launch_epi<EPI_COMBINE>(a, MT, NW, s); break;
-        case EPI_PARTIAL: launch_epi<EPI_PARTIAL>(a, MT, NW, s); break;
+        case EPI_STORE: ok = launch_epi<EPI_STORE>(a, MT, NW, NBUF, s); break;
+        case EPI_GELU: ok = launch_epi<EPI_GELU>(a, MT, NW, NBUF, s); break;
+        case EPI_SCATTER: ok = launch_epi<EPI_SCATTER>(a, MT, NW, NBUF, s); break;
+        case EPI_COMBINE: ok = launch_epi<EPI_COMBINE>(a, MT, NW, NBUF, s); break;
+        case EPI_PARTIAL: ok = launch_epi<EPI_PARTIAL>(a, MT, NW, NBUF, s); break;
         default: return MOE_ERR_INVALID_ARG;
     }
+    if (!ok) return MOE_ERR_INVALID_ARG;
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 

@@ -121,7 +121,7 @@ struct WsGemmArgs {
 };
 bool wsgemm_supported(int K, int N);
 void wsgemm_pick_tile(int max_rows, int G, int N, int* MT, int* NW);
-int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, hipStream_t s);
+int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, int NBUF, hipStream_t s);
 int wsgemm_chunk_k(int MT);   // k-extent of one LDS chunk = granularity of split-K
 
 // Sums split-K partials in split order, adds the bias and finishes like EPI_STORE (scatter_map ==
