@@ -80,6 +80,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--capacity-factor", type=float, default=None, help="experiment: override the workload's capacity factor")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -94,6 +95,8 @@ def main() -> int:
     from workloads import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    if args.capacity_factor is not None:
+        cfg = cfg.scaled(name=f"{cfg.name}-cf{args.capacity_factor}", capacity_factor=args.capacity_factor)
     inp = make_inputs(cfg, "cuda:0")
     layer = moe.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, cfg.capacity, cfg.dtype, inp.Wg, inp.bg,
                          inp.W1, inp.b1, inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)

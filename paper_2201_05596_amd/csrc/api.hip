@@ -104,7 +104,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
 
 // Carving of the caller's workspace.  Offsets in bytes; every region 256-byte aligned.
 struct WsLayout {
-    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, slot_token, xe, h, ye, hd, dense, partial, total;
+    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, order, slot_token, xe, h, ye, hd, dense, partial, total;
 };
 
 WsLayout ws_layout(const moe_shape_t* s) {
@@ -120,6 +120,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.slot_idx = take(T * k * 4);
     L.gate_w = take(T * k * 4);
     L.rows = take(E * 4);
+    L.order = take(E * 4);
     L.slot_token = take(E * C * 4);
     L.xe = take(plan.mfma ? 0 : E * C * d * es);       // the MFMA path gathers rows inside GEMM-1
     L.h = take(E * C * f * es);
@@ -157,9 +158,10 @@ inline uint16_t* u16(void* p) { return static_cast<uint16_t*>(p); }
 // Expert GEMM-1 on the MFMA kernel: h[e, r, :] = gelu_tanh(A_row(e, r) W1[e] + b1[e]).
 // row_map == nullptr: A rows are xin[e*C + r]; otherwise xin[row_map[e*C + r]] (dispatch fused in).
 int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, const int32_t* row_map,
-                     const int32_t* rows, const void* W1, const void* b1, void* h, hipStream_t st) {
+                     const int32_t* rows, const int32_t* order, const void* W1, const void* b1, void* h,
+                     hipStream_t st) {
     WsGemmArgs a{};
-    a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.row_map = row_map;
+    a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
     const int rc = launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
@@ -169,11 +171,11 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
 
 // Expert GEMM-2 on the MFMA kernel.  scatter == false: ye[e, r, :] = h[e, r, :] W2[e] + b2[e].
 // scatter == true (top-1): out[token(e, r), :] = gate_w[token] * (...), rows of dropped tokens zeroed.
-int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, const int32_t* rows, const void* W2,
-                     const void* b2, bool scatter, const int32_t* slot_token, const int32_t* slot_idx,
+int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, const int32_t* rows,
+                     const int32_t* order, const void* W2, const void* b2, bool scatter, const int32_t* slot_token, const int32_t* slot_idx,
                      const float* gate_w, void* dst, float* partial, hipStream_t st) {
     WsGemmArgs a{};
-    a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.row_map = nullptr;
+    a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.order = order; a.row_map = nullptr;
     a.max_rows = s->capacity; a.G = s->E; a.K = s->d_ffn; a.N = s->d_model;
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
@@ -264,7 +266,7 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
         if (rc != MOE_OK) return rc;
     }
     return launch_route(lg, shape->T, shape->E, shape->top_k, shape->capacity, expert_idx, slot_idx, gate_w,
-                        expert_rows, slot_token, at<int32_t>(ws, L.hist), st);
+                        expert_rows, slot_token, nullptr, at<int32_t>(ws, L.hist), st);
 }
 
 int moe_dispatch(const moe_shape_t* shape, const void* x, const int32_t* slot_token, const int32_t* expert_rows,
@@ -293,9 +295,12 @@ int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expe
     if (!plan.mfma)
         return run_ffn_simple(shape->dtype, shape->E, shape->capacity, expert_rows, 0, shape->d_model, shape->d_ffn, xe,
                               W1, b1, W2, b2, at<void>(ws, L.h), ye, st);
-    rc = run_expert_gemm1(shape, plan, xe, nullptr, expert_rows, W1, b1, at<void>(ws, L.h), st);
+    int32_t* order = at<int32_t>(ws, L.order);
+    rc = launch_expert_order(expert_rows, shape->E, shape->capacity, order, st);
     if (rc != MOE_OK) return rc;
-    return run_expert_gemm2(shape, plan, at<void>(ws, L.h), expert_rows, W2, b2, false, nullptr, nullptr, nullptr, ye,
+    rc = run_expert_gemm1(shape, plan, xe, nullptr, expert_rows, order, W1, b1, at<void>(ws, L.h), st);
+    if (rc != MOE_OK) return rc;
+    return run_expert_gemm2(shape, plan, at<void>(ws, L.h), expert_rows, order, W2, b2, false, nullptr, nullptr, nullptr, ye,
                             at<float>(ws, L.partial), st);
 }
 
@@ -344,7 +349,9 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     rc = launch_gate_logits(x, dt, Wg, bg, logits, T, d, E, st);
     prof_mark(ST_LOGITS, st);
     if (rc != MOE_OK) return rc;
-    rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, at<int32_t>(ws, L.hist), st);
+    int32_t* order = at<int32_t>(ws, L.order);
+    rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, order,
+                      at<int32_t>(ws, L.hist), st);
     prof_mark(ST_ROUTE, st);
     if (rc != MOE_OK) return rc;
     const FfnPlan plan = plan_ffn(shape);
@@ -371,13 +378,13 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     }
 
     // bf16: dispatch is fused into GEMM-1 (rows gathered through slot_token) ...
-    rc = run_expert_gemm1(shape, plan, x, slot_token, rows, W1, b1, at<void>(ws, L.h), st);
+    rc = run_expert_gemm1(shape, plan, x, slot_token, rows, order, W1, b1, at<void>(ws, L.h), st);
     if (rc != MOE_OK) return rc;
     // ... and, for top-1 Standard-MoE, combine into GEMM-2 (scale by the gate weight, write the token's row)
     if (k == 1 && !shape->residual)
-        return run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, W2, b2, true, slot_token, slot_idx, gate_w, out,
+        return run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, order, W2, b2, true, slot_token, slot_idx, gate_w, out,
                                 at<float>(ws, L.partial), st);
-    rc = run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, W2, b2, false, nullptr, nullptr, nullptr,
+    rc = run_expert_gemm2(shape, plan, at<void>(ws, L.h), rows, order, W2, b2, false, nullptr, nullptr, nullptr,
                           at<void>(ws, L.ye), at<float>(ws, L.partial), st);
     if (rc != MOE_OK) return rc;
     if (shape->residual)

@@ -62,12 +62,31 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
     // ---- which tile ------------------------------------------------------------------
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
+    // Consecutive work-group ids rotate over the 8 XCDs (each with its own L2).  With at least 8
+    // groups, all tiles of one expert are placed on one XCD: its activation rows (read by every
+    // column tile) and its weights (read by every row tile) are then fetched into that L2 once.
+    // Experts are taken from `order` (busiest first), dealt round-robin to the XCDs, so that each
+    // XCD streams the same number of active experts.  With fewer groups (the dense branch) column
+    // tiles are spread over the XCDs instead.
     const int inner_n = m_tiles * a.ksplit;
-    const int units = a.G * n_tiles;
     const int xcd = blockIdx.x % kXcd;
     const int q = blockIdx.x / kXcd;
-    const int inner = q % inner_n;
-    const int u = (q / inner_n) * kXcd + xcd;
+    int g, nt, inner;
+    bool live;
+    if (a.G >= kXcd) {
+        const int per_group = n_tiles * inner_n;
+        const int slot = (q / per_group) * kXcd + xcd;
+        nt = (q % per_group) / inner_n;
+        inner = q % inner_n;
+        live = slot < a.G;
+        g = live ? (a.order ? a.order[slot] : slot) : 0;
+    } else {
+        const int u = (q / inner_n) * kXcd + xcd;
+        g = u / n_tiles;
+        nt = u % n_tiles;
+        inner = q % inner_n;
+        live = u < a.G * n_tiles;
+    }
 
     // Top-1 combine fused into GEMM-2 leaves rows of dropped tokens unwritten: zero them here,
     // spread over all work-groups (a dropped token has no other writer).
@@ -79,8 +98,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
             }
         }
     }
-    if (u >= units) return;
-    const int g = u / n_tiles, nt = u % n_tiles;
+    if (!live) return;
     const int mt = inner % m_tiles, ks = inner / m_tiles;
     const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
     const int m0 = mt * MT;
@@ -342,8 +360,9 @@ template <int MT, int NW, int EPI, int NBUF>
 static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
-    const long long units = (long long)a.G * n_tiles;
-    const long long blocks = (units + kXcd - 1) / kXcd * kXcd * m_tiles * a.ksplit;
+    const long long per_group = (long long)n_tiles * m_tiles * a.ksplit;
+    const long long blocks = a.G >= kXcd ? (long long)(a.G + kXcd - 1) / kXcd * kXcd * per_group
+                                         : ((long long)a.G * n_tiles + kXcd - 1) / kXcd * kXcd * m_tiles * a.ksplit;
     hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a);
 }
 
@@ -354,6 +373,7 @@ static bool launch_epi(const WsGemmArgs& a, int MT, int NW, int NBUF, hipStream_
     MOE_WS_CASE(64, 4, 2) MOE_WS_CASE(64, 2, 2)
     MOE_WS_CASE(16, 4, 4) MOE_WS_CASE(16, 2, 4) MOE_WS_CASE(32, 4, 4) MOE_WS_CASE(32, 2, 4)
     MOE_WS_CASE(64, 4, 4) MOE_WS_CASE(64, 2, 4)
+    MOE_WS_CASE(16, 1, 4) MOE_WS_CASE(32, 1, 4) MOE_WS_CASE(64, 1, 4)
 #undef MOE_WS_CASE
     return false;
 }

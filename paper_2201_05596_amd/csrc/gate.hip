@@ -359,12 +359,42 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 //   second choices: row = total_1[e] + base_2[e] + rank      (all first choices rank first)
 // row >= C -> dropped (-1).  Rows >= expert_rows[e] of slot_token are set to -1.
 // ------------------------------------------------------------------------------------------
+// order[rank] = e, experts ranked by kept rows (most first, ties by index).  The expert GEMMs walk
+// this list round-robin over the XCDs, so every XCD gets the same number of active experts and the
+// long ones start first.  O(E^2) compares, E <= 1024.
+__device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */, int E, int32_t* __restrict__ order,
+                                                   int tid, int nthreads) {
+    for (int e = tid; e < E; e += nthreads) {
+        const int r = rows[e];
+        int rank = 0;
+        for (int o = 0; o < E; ++o) {
+            const int ro = rows[o];
+            rank += (ro > r || (ro == r && o < e)) ? 1 : 0;
+        }
+        order[rank] = e;
+    }
+}
+
+__global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ expert_rows, int E, int C,
+                                                           int32_t* __restrict__ order) {
+    extern __shared__ int32_t smem[];
+    for (int e = threadIdx.x; e < E; e += 256) smem[e] = min(expert_rows[e], C);
+    __syncthreads();
+    write_expert_order(smem, E, order, threadIdx.x, 256);
+}
+
+int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s) {
+    hipLaunchKernelGGL(expert_order_kernel, dim3(1), dim3(256), sizeof(int32_t) * E, s, expert_rows, E, C, order);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 template <int K>
 __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int E, int C, int nblocks,
                                                                       const int32_t* __restrict__ expert_idx,
                                                                       int32_t* __restrict__ slot_idx,
                                                                       int32_t* __restrict__ expert_rows,
                                                                       int32_t* __restrict__ slot_token,
+                                                                      int32_t* __restrict__ expert_order,
                                                                       const int32_t* __restrict__ hist) {
     extern __shared__ int32_t smem[];
     int32_t* base = smem;             // [K][E]
@@ -433,8 +463,10 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
         const int e = (int)(i / C), c = (int)(i % C);
         if (c >= rows_sh[e]) slot_token[i] = -1;
     }
-    if (b == 0)
+    if (b == 0) {
         for (int e = tid; e < E; e += kRouteTokens) expert_rows[e] = rows_sh[e];
+        if (expert_order) write_expert_order(rows_sh, E, expert_order, tid, kRouteTokens);
+    }
 }
 
 size_t route_scratch_ints(int T, int E, int k) {
@@ -443,7 +475,8 @@ size_t route_scratch_ints(int T, int E, int k) {
 }
 
 int launch_route(const float* logits, int T, int E, int k, int C, int32_t* expert_idx, int32_t* slot_idx,
-                 float* gate_w, int32_t* expert_rows, int32_t* slot_token, int32_t* scratch, hipStream_t s) {
+                 float* gate_w, int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order, int32_t* scratch,
+                 hipStream_t s) {
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const int NW = kRouteTokens / kWave;
     const size_t sm1 = sizeof(int32_t) * ((size_t)k * kRouteTokens + (size_t)NW * k * E);
@@ -460,7 +493,7 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
         else if (E <= 128) MOE_ROUTE_LOCAL(1, 8);
         else MOE_ROUTE_LOCAL(1, 0);
         hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
-                           expert_idx, slot_idx, expert_rows, slot_token, scratch);
+                           expert_idx, slot_idx, expert_rows, slot_token, expert_order, scratch);
     } else {
         if (E <= 16) MOE_ROUTE_LOCAL(2, 1);
         else if (E <= 32) MOE_ROUTE_LOCAL(2, 2);
@@ -468,7 +501,7 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
         else if (E <= 128) MOE_ROUTE_LOCAL(2, 8);
         else MOE_ROUTE_LOCAL(2, 0);
         hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
-                           expert_idx, slot_idx, expert_rows, slot_token, scratch);
+                           expert_idx, slot_idx, expert_rows, slot_token, expert_order, scratch);
     }
 #undef MOE_ROUTE_LOCAL
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;

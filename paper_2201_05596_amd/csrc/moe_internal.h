@@ -57,7 +57,11 @@ size_t route_scratch_ints(int T, int E, int k);
 // softmax + top-k + capacity slots from fp32 logits
 int launch_route(const float* logits, int T, int E, int k, int C,
                  int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
-                 int32_t* expert_rows, int32_t* slot_token, int32_t* scratch, hipStream_t s);
+                 int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order /* [E] or nullptr */,
+                 int32_t* scratch, hipStream_t s);
+
+// order[rank] = expert, ranked by min(expert_rows, C) descending (ties by index)
+int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s);
 
 int launch_dispatch(const void* x, int dtype, const int32_t* slot_token, const int32_t* expert_rows,
                     void* xe, int E, int C, int d, hipStream_t s);
@@ -97,6 +101,7 @@ struct WsGemmArgs {
     const uint16_t* B;         // [G, K, N]
     const uint16_t* bias;      // [G, N] or nullptr
     const int32_t* rows;       // [G] device row counts or nullptr -> fixed_rows
+    const int32_t* order;      // [G] groups in launch order (busiest first) or nullptr -> identity
     const int32_t* row_map;    // [G, map_stride]: A-row of (g, r), or nullptr -> g*a_group_stride + r
     int32_t fixed_rows, max_rows, map_stride;
     int32_t G, K, N;
