@@ -76,7 +76,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
     FfnPlan p{};
     p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
     p.ksplit2 = 1;
-    p.NBUF = tune("MOE_TUNE_NBUF") ? tune("MOE_TUNE_NBUF") : 2;
+    p.NBUF = tune("MOE_TUNE_NBUF") ? tune("MOE_TUNE_NBUF") : 4;
     if (!p.mfma) return p;
     wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
     int mt2;
@@ -210,14 +210,14 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
-    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, 2, st);
+    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
     prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
     a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
     a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
-    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, 2, st);
+    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, 4, st);
     prof_mark(ST_DENSE2, st);
     return rc;
 }

@@ -206,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
         for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
         a_load(ch_beg);
         a_store(ch_beg, 0);
-        __syncthreads();
+        lds_barrier();
 
         const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
         for (int ch = ch_beg; ch < ch_end; ++ch) {
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
                 }
             }
             a_store(ch + 1, buf ^ 1);
-            __syncthreads();
+            lds_barrier();
         }
     }
 

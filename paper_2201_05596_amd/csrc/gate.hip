@@ -8,6 +8,8 @@
 // scan on its hardware; here the count is done with 64-wide wavefront ballots
 // (rank inside a wave), a per-block histogram and a prefix over blocks, which
 // is deterministic (no atomics) and needs two small launches.
+#include <cstdlib>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -25,33 +27,49 @@ namespace moe {
 // every CU busy when there are few tokens).
 // ------------------------------------------------------------------------------------------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
-constexpr int kGK = 32;      // k-chunk
+constexpr int kGK = 32;      // k-rows per step
+constexpr int kGPD = 3;      // steps of operands kept in flight in registers
 
-__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
-    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-__device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
-    const uint4 a = *reinterpret_cast<const uint4*>(p);
-    v[0] = __uint_as_float(a.x << 16); v[1] = __uint_as_float(a.x & 0xffff0000u);
-    v[2] = __uint_as_float(a.y << 16); v[3] = __uint_as_float(a.y & 0xffff0000u);
-    v[4] = __uint_as_float(a.z << 16); v[5] = __uint_as_float(a.z & 0xffff0000u);
-    v[6] = __uint_as_float(a.w << 16); v[7] = __uint_as_float(a.w & 0xffff0000u);
-}
-// 4 consecutive k (fp32 rows whose length is a multiple of 4 but not of 8)
-__device__ __forceinline__ void load4(const float* p, float* v) {
-    const float4 a = *reinterpret_cast<const float4*>(p);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-}
+// 8 consecutive k of a token row as raw 16-byte words (bf16: one word; fp32: two), widened later
+template <typename XT> struct XRaw;
+template <> struct XRaw<uint16_t> {
+    uint4 w;
+    __device__ __forceinline__ void load(const uint16_t* row, int k, int d) {
+        w = *reinterpret_cast<const uint4*>(row + min(k, d - 8));
+    }
+    __device__ __forceinline__ void widen(int k, int d, float (&v)[8]) const {
+        const bool in = k < d;                              // d % 8 == 0: all eight or none
+        const uint4 a = in ? w : make_uint4(0, 0, 0, 0);
+        v[0] = __uint_as_float(a.x << 16); v[1] = __uint_as_float(a.x & 0xffff0000u);
+        v[2] = __uint_as_float(a.y << 16); v[3] = __uint_as_float(a.y & 0xffff0000u);
+        v[4] = __uint_as_float(a.z << 16); v[5] = __uint_as_float(a.z & 0xffff0000u);
+        v[6] = __uint_as_float(a.w << 16); v[7] = __uint_as_float(a.w & 0xffff0000u);
+    }
+};
+template <> struct XRaw<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const float* row, int k, int d) {
+        lo = *reinterpret_cast<const float4*>(row + min(k, d - 4));
+        hi = *reinterpret_cast<const float4*>(row + min(k + 4, d - 4));
+    }
+    __device__ __forceinline__ void widen(int k, int d, float (&v)[8]) const {
+        const bool in0 = k < d, in1 = k + 4 < d;            // d % 4 == 0
+        v[0] = in0 ? lo.x : 0.f; v[1] = in0 ? lo.y : 0.f; v[2] = in0 ? lo.z : 0.f; v[3] = in0 ? lo.w : 0.f;
+        v[4] = in1 ? hi.x : 0.f; v[5] = in1 ? hi.y : 0.f; v[6] = in1 ? hi.z : 0.f; v[7] = in1 ? hi.w : 0.f;
+    }
+};
 
-template <typename XT, int WT, int WE, int WK>
+// VEC = 4: E is a multiple of 4 and Wg rows are read as float4; VEC = 1: any E, scalar reads.
+// FULL: d is a multiple of 32*WK and E of the work-group's expert width, so no operand is ever out
+// of range and the selects that zero them disappear from the loop.
+template <typename XT, int WT, int WE, int WK, int VEC, bool FULL>
 __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__ x, const float* __restrict__ Wg,
                                                           const float* __restrict__ bg, float* __restrict__ logits,
                                                           int T, int d, int E) {
     static_assert(WT * WE * WK == 4, "four waves");
-    constexpr int EN = WE * 64;                 // experts per pass of the work-group
-    constexpr int TM = WT * 16;                 // tokens per work-group
-    constexpr int NB = WK * kGK * EN / 256;     // Wg elements staged per thread and pass
+    constexpr int EN = WE * 64;                       // experts per pass of the work-group
+    constexpr int TM = WT * 16;                       // tokens per work-group
+    constexpr int NB = WK * kGK * EN / 256 / VEC;     // Wg words staged per thread and step
     __shared__ __attribute__((aligned(16))) float Bs[WK][kGK][EN];
     __shared__ float red[WK > 1 ? (WK - 1) * WT * WE * 16 * 64 : 1];
 
@@ -59,12 +77,13 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__
     const int n = lane & 15, g = lane >> 4;
     const int wk = w % WK, we = (w / WK) % WE, wt = w / (WK * WE);
     const int t0 = blockIdx.x * TM + wt * 16;
-    const int trow = min(t0 + n, T - 1);                            // A row of this lane (clamped, not stored)
-    const XT* xrow = x + (size_t)trow * d;
+    const XT* xrow = x + (size_t)min(t0 + n, T - 1) * d;           // A row of this lane (clamped, not stored)
 
-    // k is cut into 32-wide chunks; split s of the WK k-splits owns chunks [s*cper, (s+1)*cper).
-    // In pass c the work-group stages chunk s*cper + c of every split, and each wave multiplies
-    // its own split's tile.
+    // k is cut into 32-row chunks; split s of the WK k-splits owns chunks [s*cper, (s+1)*cper).
+    // In step c the work-group stages chunk s*cper + c of every split and each wave multiplies its
+    // own split's tile.  Operands of the next kGPD steps are always in flight: all loads are
+    // unconditional (addresses clamped, values zeroed when consumed), so no branch separates a load
+    // from its use and the compiler can count outstanding loads exactly.
     const int chunks = (d + kGK - 1) / kGK;
     const int cper = (chunks + WK - 1) / WK;
 
@@ -73,56 +92,70 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        float breg[NB];
-        auto b_load = [&](int c) {
+        typedef float bword_t __attribute__((ext_vector_type(VEC)));
+        bword_t breg[kGPD][NB];
+        XRaw<XT> areg[kGPD];
+
+        auto b_load = [&](bword_t (&dst)[NB], int c) {
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                const int p = tid + i * 256;
+                const int p = (tid + i * 256) * VEC;
                 const int s = p / (kGK * EN), kk = (p / EN) % kGK, ee = p % EN;
-                const int ch = s * cper + c;
-                const int k = ch * kGK + kk, e = e0 + ee;
-                breg[i] = (c < cper && k < d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
+                const int k = min((s * cper + c) * kGK + kk, d - 1), e = min(e0 + ee, E - VEC);
+                dst[i] = *reinterpret_cast<const bword_t*>(Wg + (size_t)k * E + e);
             }
         };
-        auto b_store = [&]() {
+        auto b_store = [&](const bword_t (&src)[NB], int c) {
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                const int p = tid + i * 256;
+                const int p = (tid + i * 256) * VEC;
                 const int s = p / (kGK * EN), kk = (p / EN) % kGK, ee = p % EN;
-                Bs[s][kk][(ee + 16 * (kk >> 3)) % EN] = breg[i];
+                bword_t v = src[i];
+                if (!FULL) {
+                    const bool in = (s * cper + c) * kGK + kk < d && e0 + ee < E && c < cper;
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) v[q] = in ? v[q] : 0.f;
+                }
+                // columns rotated by 16 per 8 rows: the four lane groups of a B read hit distinct banks
+                *reinterpret_cast<bword_t*>(&Bs[s][kk][(ee + 16 * (kk >> 3)) % EN]) = v;
             }
         };
-        auto a_load = [&](int c, float (&v)[8]) {
-            const int k = (wk * cper + c) * kGK + 8 * g;
-            if (c < cper && k + 8 <= d) {
-                load8(xrow + k, v);
-            } else {
+        // one step: tile of chunk c to LDS, refill the register slot kGPD steps ahead, multiply
+        auto step = [&](bword_t (&bslot)[NB], XRaw<XT>& aslot, int c) {
+            lds_barrier();                            // the previous step has finished reading the tile
+            b_store(bslot, c);
+            float av[8];
+            const int ka = (wk * cper + c) * kGK + 8 * g;
+            aslot.widen(FULL ? 0 : (c < cper ? ka : d), d, av);
+            lds_barrier();
+            b_load(bslot, c + kGPD);
+            aslot.load(xrow, (wk * cper + c + kGPD) * kGK + 8 * g, d);
+            __builtin_amdgcn_sched_barrier(0);
+            float bv[8][4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = 0.f;
-                if (sizeof(XT) == 4 && c < cper && k + 4 <= d) load4(reinterpret_cast<const float*>(xrow) + k, v);
-            }
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) bv[j][nt] = Bs[wk][8 * g + j][(we * 64 + nt * 16 + n + 16 * g) % EN];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j], bv[j][nt], acc[nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         };
 
-        float av[8], av_next[8];
-        b_load(0);
-        a_load(0, av_next);
-        for (int c = 0; c < cper; ++c) {
-            __syncthreads();                 // the previous pass has finished reading the tile
-            b_store();
-            __syncthreads();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) av[j] = av_next[j];
-            b_load(c + 1);                   // prefetch the next pass while this one is multiplied
-            a_load(c + 1, av_next);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    const float b = Bs[wk][8 * g + j][(we * 64 + nt * 16 + n + 16 * g) % EN];
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j], b, acc[nt], 0, 0, 0);
-                }
-            }
+        for (int s = 0; s < kGPD; ++s) {
+            b_load(breg[s], s);
+            areg[s].load(xrow, (wk * cper + s) * kGK + 8 * g, d);
         }
+        int c0 = 0;
+        for (; c0 + kGPD <= cper; c0 += kGPD) {
+#pragma unroll
+            for (int s = 0; s < kGPD; ++s) step(breg[s], areg[s], c0 + s);
+        }
+        if (c0 < cper) step(breg[0], areg[0], c0);
+        if (c0 + 1 < cper) step(breg[1], areg[1], c0 + 1);
 
         if (WK > 1) {
             __syncthreads();
@@ -157,17 +190,30 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__
                 }
             }
         }
+        __syncthreads();      // the next expert pass restages the tile
     }
 }
 
 template <typename XT>
 static int launch_logits_t(const XT* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
                            hipStream_t s) {
-#define MOE_LOGITS_CASE(WT, WE, WK)                                                                       \
-    hipLaunchKernelGGL((gate_logits_kernel<XT, WT, WE, WK>), dim3((T + WT * 16 - 1) / (WT * 16)), dim3(256), 0, \
-                       s, x, Wg, bg, logits, T, d, E)
+#define MOE_LOGITS_CASE(WT, WE, WK)                                                                          \
+    do {                                                                                                     \
+        const dim3 grid((T + WT * 16 - 1) / (WT * 16));                                                      \
+        const bool full = d % (kGK * WK) == 0 && E % (WE * 64) == 0;                                         \
+        if (full)                                                                                            \
+            hipLaunchKernelGGL((gate_logits_kernel<XT, WT, WE, WK, 4, true>), grid, dim3(256), 0, s, x, Wg, bg,     \
+                               logits, T, d, E);                                                             \
+        else if (E % 4 == 0)                                                                                 \
+            hipLaunchKernelGGL((gate_logits_kernel<XT, WT, WE, WK, 4, false>), grid, dim3(256), 0, s, x, Wg, bg,    \
+                               logits, T, d, E);                                                             \
+        else                                                                                                 \
+            hipLaunchKernelGGL((gate_logits_kernel<XT, WT, WE, WK, 1, false>), grid, dim3(256), 0, s, x, Wg, bg,    \
+                               logits, T, d, E);                                                             \
+    } while (0)
     const bool wide = E > 64;          // 128 experts per pass, else 64
-    const bool few = T <= 1024;        // few tokens: spend waves on k-splits instead of token tiles
+    const char* tune_env = getenv("MOE_TUNE_LOGITS_FEW");
+    const bool few = tune_env ? atoi(tune_env) != 0 : T <= 1024;   // few tokens: waves go to k-splits, not token tiles
     if (wide) {
         if (few) MOE_LOGITS_CASE(1, 2, 2);
         else MOE_LOGITS_CASE(2, 2, 1);
@@ -201,70 +247,99 @@ struct Best {
 __device__ __forceinline__ Best better(Best a, Best b) {
     return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
 }
-// reductions inside aligned groups of 16 lanes (xor masks < 16 never leave the group)
+// All-reduce inside aligned groups of 16 lanes (one DPP "row") with data-parallel-primitive moves:
+// swap inside pairs, swap pairs inside quads, mirror the two quads of each half row, mirror the two
+// half rows.  After step i every aligned group of 2^i lanes holds one common value, which is what
+// makes the mirrors (which reverse lane order) as good as butterflies.  No LDS traffic, unlike
+// __shfl_xor.
+constexpr int kDppSwap1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppSwap2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror
+constexpr int kDppMirror = 0x140;      // row_mirror
+template <int CTRL> __device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(dpp_i<CTRL>(__float_as_int(v)));
+}
+template <int CTRL> __device__ __forceinline__ Best best_step(Best a) {
+    Best o;
+    o.v = dpp_f<CTRL>(a.v);
+    o.i = dpp_i<CTRL>(a.i);
+    return better(a, o);
+}
 __device__ __forceinline__ Best group_best(Best a) {
-#pragma unroll
-    for (int m = 8; m >= 1; m >>= 1) {
-        Best o;
-        o.v = __shfl_xor(a.v, m, kWave);
-        o.i = __shfl_xor(a.i, m, kWave);
-        a = better(a, o);
-    }
+    a = best_step<kDppSwap1>(a);
+    a = best_step<kDppSwap2>(a);
+    a = best_step<kDppHalfMirror>(a);
+    a = best_step<kDppMirror>(a);
     return a;
 }
+// Sum in a fixed tree order; every lane ends with the same bits (each step adds the same two
+// partial sums on both sides, and fp add commutes).
 __device__ __forceinline__ float group_sum(float a) {
-#pragma unroll
-    for (int m = 8; m >= 1; m >>= 1) a += __shfl_xor(a, m, kWave);
+    a += dpp_f<kDppSwap1>(a);
+    a += dpp_f<kDppSwap2>(a);
+    a += dpp_f<kDppHalfMirror>(a);
+    a += dpp_f<kDppMirror>(a);
     return a;
 }
 
-// Top-K experts and gate weights of one token, computed by a group of 16 lanes; lane `sub` looks
-// at experts sub, sub+16, ...  NV > 0: the row fits NV registers per lane (E <= 16*NV), one pass.
-// NV == 0: any E, two passes over the row.  Every lane of the group returns the same result.
-template <int K, int NV>
-__device__ __forceinline__ void token_gate(const float* __restrict__ row, int E, int sub, Best& g1, Best& g2,
-                                           float& w1, float& w2) {
-    const Best none{-INFINITY, 0x7fffffff};
-    Best b1 = none, b2 = none;
-    float s = 0.f;
-    if (NV > 0) {
-        float v[NV > 0 ? NV : 1];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int e = sub + 16 * i;
-            v[i] = e < E ? row[e] : -INFINITY;
-        }
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int e = sub + 16 * i;
-            if (v[i] > b1.v) { b2 = b1; b1.v = v[i]; b1.i = e; }
-            else if (v[i] > b2.v) { b2.v = v[i]; b2.i = e; }
-        }
-        g1 = group_best(b1);
-        g2 = none;
-        if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) s += expf(v[i] - g1.v);       // exp(-inf) = 0 for the padding
-    } else {
-        for (int e = sub; e < E; e += 16) {
-            const float v = row[e];
-            if (v > b1.v) { b2 = b1; b1.v = v; b1.i = e; }
-            else if (v > b2.v) { b2.v = v; b2.i = e; }
-        }
-        g1 = group_best(b1);
-        g2 = none;
-        if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
-        for (int e = sub; e < E; e += 16) s += expf(row[e] - g1.v);
-    }
-    s = group_sum(s);
+// exp on the hardware exp2 unit; the argument is <= 0 here and the dominant terms have a small
+// argument, which keeps the softmax weights within ~1e-7 of the exact value
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+
+template <int K>
+__device__ __forceinline__ void gate_weights(float s, Best g1, Best g2, float& w1, float& w2) {
     if (K == 1) {
-        w1 = 1.0f / s;                       // softmax probability of the arg-max
+        w1 = 1.0f / s;                          // softmax probability of the arg-max
         w2 = 0.f;
     } else {
-        const float r = expf(g2.v - g1.v);   // p2/p1; renormalised pair = (1, r)/(1 + r)
+        const float r = fast_exp(g2.v - g1.v);  // p2/p1; renormalised pair = (1, r)/(1 + r)
         w1 = 1.0f / (1.0f + r);
         w2 = r / (1.0f + r);
     }
+}
+
+// Top-K experts and gate weights of one token, computed by a group of 16 lanes; lane `sub` looks
+// at experts sub, sub+16, ...  Every lane of the group returns the same result.
+// Register version: the lane's NV logits are already loaded (padding = -inf).
+template <int K, int NV>
+__device__ __forceinline__ void token_gate_regs(const float (&v)[NV], int sub, Best& g1, Best& g2, float& w1,
+                                                float& w2) {
+    const Best none{-INFINITY, 0x7fffffff};
+    Best b1 = none, b2 = none;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int e = sub + 16 * i;
+        if (v[i] > b1.v) { b2 = b1; b1.v = v[i]; b1.i = e; }
+        else if (v[i] > b2.v) { b2.v = v[i]; b2.i = e; }
+    }
+    g1 = group_best(b1);
+    g2 = none;
+    if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += fast_exp(v[i] - g1.v);       // exp(-inf) = 0 for the padding
+    gate_weights<K>(group_sum(s), g1, g2, w1, w2);
+}
+// Any E: two passes over the row in memory.
+template <int K>
+__device__ __forceinline__ void token_gate_mem(const float* __restrict__ row, int E, int sub, Best& g1, Best& g2,
+                                               float& w1, float& w2) {
+    const Best none{-INFINITY, 0x7fffffff};
+    Best b1 = none, b2 = none;
+    for (int e = sub; e < E; e += 16) {
+        const float v = row[e];
+        if (v > b1.v) { b2 = b1; b1.v = v; b1.i = e; }
+        else if (v > b2.v) { b2.v = v; b2.i = e; }
+    }
+    g1 = group_best(b1);
+    g2 = none;
+    if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
+    float s = 0.f;
+    for (int e = sub; e < E; e += 16) s += fast_exp(row[e] - g1.v);
+    gate_weights<K>(group_sum(s), g1, g2, w1, w2);
 }
 
 template <int K, int NV>
@@ -283,17 +358,13 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 
     for (int i = tid; i < NW * K * E; i += kRouteTokens) whist[i] = 0;
 
-    // phase A: 16 lanes per token, 16 tokens of the block at a time
+    // phase A: 16 lanes per token, 16 tokens of the block at a time.  When the row fits in registers
+    // (E <= 128) the logits of all 16 rounds are fetched first, in one memory round trip.
     {
         const int grp = tid >> 4, sub = tid & 15;
-#pragma unroll 4
-        for (int it = 0; it < kRouteTokens / 16; ++it) {
-            const int tl = it * 16 + grp;
+        constexpr int ROUNDS = kRouteTokens / 16;
+        auto publish = [&](int tl, Best g1, Best g2, float w1, float w2) {
             const int t = tb + tl;
-            const int tc = min(t, T - 1);                 // clamp: all lanes stay in the shuffles
-            Best g1, g2;
-            float w1, w2;
-            token_gate<K, NV>(logits + (size_t)tc * E, E, sub, g1, g2, w1, w2);
             if (sub == 0) {
                 const bool ok = t < T;
                 e_sh[tl] = ok ? g1.i : -1;
@@ -306,6 +377,34 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
                         gate_w[(size_t)t * K + 1] = w2;
                     }
                 }
+            }
+        };
+        if (NV > 0) {
+            constexpr int NVV = NV > 0 ? NV : 1;
+            float v[ROUNDS][NVV];
+#pragma unroll
+            for (int it = 0; it < ROUNDS; ++it) {
+                const float* row = logits + (size_t)min(tb + it * 16 + grp, T - 1) * E;   // clamped: lanes stay in the shuffles
+#pragma unroll
+                for (int i = 0; i < NVV; ++i) v[it][i] = row[min(sub + 16 * i, E - 1)];
+            }
+#pragma unroll
+            for (int it = 0; it < ROUNDS; ++it) {
+#pragma unroll
+                for (int i = 0; i < NVV; ++i) v[it][i] = sub + 16 * i < E ? v[it][i] : -INFINITY;
+                Best g1, g2;
+                float w1, w2;
+                token_gate_regs<K, NVV>(v[it], sub, g1, g2, w1, w2);
+                publish(it * 16 + grp, g1, g2, w1, w2);
+            }
+        } else {
+#pragma unroll 4
+            for (int it = 0; it < ROUNDS; ++it) {
+                const int tl = it * 16 + grp;
+                Best g1, g2;
+                float w1, w2;
+                token_gate_mem<K>(logits + (size_t)min(tb + tl, T - 1) * E, E, sub, g1, g2, w1, w2);
+                publish(tl, g1, g2, w1, w2);
             }
         }
     }

@@ -11,6 +11,15 @@ namespace moe {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kRouteTokens = 256;    // tokens per block in the routing kernels
 
+// Work-group barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding
+// global load (on gfx9 loads and stores share one counter), which would empty the register prefetch
+// queues the streaming kernels depend on at each barrier.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---- bf16 <-> f32 on raw 16-bit patterns -------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t v) {
     return __uint_as_float(static_cast<uint32_t>(v) << 16);
