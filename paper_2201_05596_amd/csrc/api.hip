@@ -63,6 +63,7 @@ struct FfnPlan {
     bool mfma;          // false: plain fp32-ALU GEMM (fp32 layers)
     int MT, NW1, NW2;   // row tile; waves per work-group of GEMM-1 / GEMM-2
     int ksplit2;        // split-K factor of GEMM-2 (1 = none)
+    bool tiled;         // more than 64 rows per expert: the tiled (matrix-core-bound) kernel
     int NBUF;           // weight super-fragments kept in flight per wave, plus one
 };
 
@@ -78,6 +79,8 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
     p.ksplit2 = 1;
     p.NBUF = tune("MOE_TUNE_NBUF") ? tune("MOE_TUNE_NBUF") : 4;
     if (!p.mfma) return p;
+    p.tiled = s->capacity > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
+              !tune("MOE_TUNE_NOTILE");
     wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
     int mt2;
     wsgemm_pick_tile(s->capacity, s->E, s->d_model, &mt2, &p.NW2);
@@ -88,7 +91,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
     const long long touched = s->E < (long long)s->T * s->top_k ? s->E : (long long)s->T * s->top_k;
     const long long m_tiles = (s->capacity + p.MT - 1) / p.MT;
     const long long waves = touched * ((s->d_model + 127) / 128) * m_tiles;
-    if (waves < 1024) {
+    if (waves < 1024 && !p.tiled) {
         const int chunks = (s->d_ffn + wsgemm_chunk_k(p.MT) - 1) / wsgemm_chunk_k(p.MT);
         long long ks = (2048 + waves - 1) / waves;
         if (ks > 8) ks = 8;
@@ -164,7 +167,7 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
-    const int rc = launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
+    const int rc = p.tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
     prof_mark(ST_GEMM1, st);
     return rc;
 }
@@ -181,7 +184,8 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
     if (p.ksplit2 == 1) {
-        const int rc1 = launch_wsgemm(a, scatter ? EPI_SCATTER : EPI_STORE, p.MT, p.NW2, p.NBUF, st);
+        const int epi = scatter ? EPI_SCATTER : EPI_STORE;
+        const int rc1 = p.tiled ? launch_tgemm(a, epi, st) : launch_wsgemm(a, epi, p.MT, p.NW2, p.NBUF, st);
         prof_mark(ST_GEMM2, st);
         return rc1;
     }
@@ -210,14 +214,16 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
-    int rc = launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
+    const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
+                       !tune("MOE_TUNE_NOTILE");
+    int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
     prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
     a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
     a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
-    rc = launch_wsgemm(a, EPI_COMBINE, MT, NW, 4, st);
+    rc = tiled ? launch_tgemm(a, EPI_COMBINE, st) : launch_wsgemm(a, EPI_COMBINE, MT, NW, 4, st);
     prof_mark(ST_DENSE2, st);
     return rc;
 }

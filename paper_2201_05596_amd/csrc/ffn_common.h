@@ -1,0 +1,144 @@
+// Pieces shared by the two bf16 MFMA grouped-GEMM kernels (weight-streaming and tiled): operand
+// types, the register transpose of K-major weights, the XCD-aware tile numbering and the epilogues.
+#pragma once
+
+#include "moe_internal.h"
+
+namespace moe {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kXcd = 8;             // L2 domains; consecutive work-group ids rotate over them
+
+__device__ __forceinline__ uint32_t dw(const uint4& v, int q) {
+    return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
+}
+
+// MFMA B fragments from K-major weights.  src[j] holds 8 consecutive columns of k-row j (j = 0..7):
+// an 8x8 block of 16-bit values, k down, n across.  The MFMA wants, per output column, 8 consecutive
+// k in one register quad: an 8x8 transpose, done with v_perm_b32.  Pair qq of the block's columns
+// (2qq, 2qq+1) comes out as two fragments.
+__device__ __forceinline__ void b_frag_pair(const uint4 (&src)[8], int qq, bf16x8_t& lo_col, bf16x8_t& hi_col) {
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t r0 = dw(src[2 * p], qq), r1 = dw(src[2 * p + 1], qq);
+        lo[p] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);   // column 2qq   : k = 2p, 2p+1
+        hi[p] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // column 2qq+1
+    }
+    lo_col = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    hi_col = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+}
+
+// Consecutive work-group ids rotate over the 8 XCDs (each with its own L2).  With at least 8
+// groups, all tiles of one expert are placed on one XCD: its activation rows (read by every
+// column tile) and its weights (read by every row tile) are then fetched into that L2 once.
+// Experts are taken from `order` (busiest first), dealt round-robin to the XCDs, so that each
+// XCD streams the same number of active experts.  With fewer groups (the dense branch) column
+// tiles are spread over the XCDs instead.  inner_n = row tiles x k-splits per (group, column tile).
+struct TileId {
+    int g, nt, inner;
+    bool live;
+};
+__device__ __forceinline__ TileId tile_of_block(const WsGemmArgs& a, int n_tiles, int inner_n) {
+    TileId t;
+    const int xcd = blockIdx.x % kXcd;
+    const int q = blockIdx.x / kXcd;
+    if (a.G >= kXcd) {
+        const int per_group = n_tiles * inner_n;
+        const int slot = (q / per_group) * kXcd + xcd;
+        t.nt = (q % per_group) / inner_n;
+        t.inner = q % inner_n;
+        t.live = slot < a.G;
+        t.g = t.live ? (a.order ? a.order[slot] : slot) : 0;
+    } else if (a.ksplit == 1 && inner_n >= kXcd) {
+        // few groups with many row tiles (the dense branch): every XCD takes a contiguous range of
+        // row tiles and walks it column tile by column tile, so the work-groups running together on
+        // an XCD share a few activation row tiles (kept in its L2) while the weights stream through
+        const int per_xcd = (inner_n + kXcd - 1) / kXcd;
+        const int per_group = per_xcd * n_tiles;
+        t.g = q / per_group;
+        t.nt = q % n_tiles;
+        t.inner = xcd * per_xcd + (q % per_group) / n_tiles;
+        t.live = t.g < a.G && t.inner < inner_n;
+    } else {
+        const int u = (q / inner_n) * kXcd + xcd;
+        t.g = u / n_tiles;
+        t.nt = u % n_tiles;
+        t.inner = q % inner_n;
+        t.live = u < a.G * n_tiles;
+    }
+    return t;
+}
+inline long long tile_grid_blocks(const WsGemmArgs& a, int n_tiles, int inner_n) {
+    if (a.G >= kXcd) return (long long)(a.G + kXcd - 1) / kXcd * kXcd * n_tiles * inner_n;
+    if (a.ksplit == 1 && inner_n >= kXcd) return (long long)a.G * ((inner_n + kXcd - 1) / kXcd) * n_tiles * kXcd;
+    return ((long long)a.G * n_tiles + kXcd - 1) / kXcd * kXcd * inner_n;
+}
+
+// Top-1 combine fused into GEMM-2 leaves rows of dropped tokens unwritten: zero them, spread over
+// all work-groups (a dropped token has no other writer).
+__device__ __forceinline__ void zero_dropped_rows(const WsGemmArgs& a, int tid, int nthreads) {
+    if (!a.zero_slot_idx) return;
+    for (int t = blockIdx.x; t < a.T; t += gridDim.x) {
+        if (a.zero_slot_idx[t] < 0) {
+            uint4* o = reinterpret_cast<uint4*>(a.out + (size_t)t * a.N);
+            for (int i = tid; i < a.N / 8; i += nthreads) o[i] = make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
+__device__ __forceinline__ void load_bias8(const WsGemmArgs& a, int g, int n_lane, float (&bias)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+    if (a.bias) {
+        const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + n_lane);
+        bias[0] = __uint_as_float(bv.x << 16); bias[1] = __uint_as_float(bv.x & 0xffff0000u);
+        bias[2] = __uint_as_float(bv.y << 16); bias[3] = __uint_as_float(bv.y & 0xffff0000u);
+        bias[4] = __uint_as_float(bv.z << 16); bias[5] = __uint_as_float(bv.z & 0xffff0000u);
+        bias[6] = __uint_as_float(bv.w << 16); bias[7] = __uint_as_float(bv.w & 0xffff0000u);
+    }
+}
+
+// Finishes 8 consecutive columns n_lane.. of row `row` (index inside group g): v = acc + bias on entry.
+template <int EPI>
+__device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, int ks, int n_lane, float (&v)[8]) {
+    const long long grow = (long long)g * a.o_group_stride + row;   // row in [G, o_group_stride]
+    if (EPI == EPI_PARTIAL) {
+        float* o = a.partial + ((size_t)ks * a.partial_rows + grow) * a.N + n_lane;
+        *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        return;
+    }
+    size_t orow = (size_t)grow;
+    if (EPI == EPI_GELU) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = gelu_tanh(v[i]);
+    } else if (EPI == EPI_SCATTER) {
+        const int t = a.scatter_map[(size_t)g * a.scatter_stride + row];   // token of this expert row
+        const float gw = a.gate_w[(size_t)t * a.top_k];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] *= gw;
+        orow = (size_t)t;
+    } else if (EPI == EPI_COMBINE) {
+        // dense branch + sum_j keep_j g_j ye[e_j, slot_j, :] for token grow
+        for (int j = 0; j < a.top_k; ++j) {
+            const int s = a.slot_idx[grow * a.top_k + j];
+            if (s < 0) continue;
+            const int e = a.expert_idx[grow * a.top_k + j];
+            const float gw = a.gate_w[grow * a.top_k + j];
+            const uint4 yv = *reinterpret_cast<const uint4*>(a.ye + ((size_t)e * a.C + s) * a.N + n_lane);
+            v[0] = fmaf(gw, __uint_as_float(yv.x << 16), v[0]); v[1] = fmaf(gw, __uint_as_float(yv.x & 0xffff0000u), v[1]);
+            v[2] = fmaf(gw, __uint_as_float(yv.y << 16), v[2]); v[3] = fmaf(gw, __uint_as_float(yv.y & 0xffff0000u), v[3]);
+            v[4] = fmaf(gw, __uint_as_float(yv.z << 16), v[4]); v[5] = fmaf(gw, __uint_as_float(yv.z & 0xffff0000u), v[5]);
+            v[6] = fmaf(gw, __uint_as_float(yv.w << 16), v[6]); v[7] = fmaf(gw, __uint_as_float(yv.w & 0xffff0000u), v[7]);
+        }
+    }
+    uint4 o;
+    o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
+    o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane) = o;
+}
+
+}  // namespace moe

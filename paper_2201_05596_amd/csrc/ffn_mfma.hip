@@ -26,21 +26,13 @@
 //   * v_mfma_f32_16x16x32_bf16, fp32 accumulation.
 // Work-groups are numbered so that all row tiles of one (expert, column tile)
 // run on the same XCD back to back and share the weights through that XCD's L2.
-#include "moe_internal.h"
+#include "ffn_common.h"
 
 namespace moe {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-constexpr int kXcd = 8;             // L2 domains; consecutive work-group ids rotate over them
 constexpr int kSF = 32;             // k-rows per super-fragment (one 16x16x32 MFMA deep)
 constexpr int kWaveCols = 128;      // output columns per wave
 constexpr int kLdsTileElems = 8192; // MT * KC: bf16 elements of one LDS activation buffer
-
-__device__ __forceinline__ uint32_t dw(const uint4& v, int q) {
-    return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
-}
 
 template <int MT, int NW, int EPI, int NBUF>
 __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
@@ -62,43 +54,12 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
     // ---- which tile ------------------------------------------------------------------
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
-    // Consecutive work-group ids rotate over the 8 XCDs (each with its own L2).  With at least 8
-    // groups, all tiles of one expert are placed on one XCD: its activation rows (read by every
-    // column tile) and its weights (read by every row tile) are then fetched into that L2 once.
-    // Experts are taken from `order` (busiest first), dealt round-robin to the XCDs, so that each
-    // XCD streams the same number of active experts.  With fewer groups (the dense branch) column
-    // tiles are spread over the XCDs instead.
     const int inner_n = m_tiles * a.ksplit;
-    const int xcd = blockIdx.x % kXcd;
-    const int q = blockIdx.x / kXcd;
-    int g, nt, inner;
-    bool live;
-    if (a.G >= kXcd) {
-        const int per_group = n_tiles * inner_n;
-        const int slot = (q / per_group) * kXcd + xcd;
-        nt = (q % per_group) / inner_n;
-        inner = q % inner_n;
-        live = slot < a.G;
-        g = live ? (a.order ? a.order[slot] : slot) : 0;
-    } else {
-        const int u = (q / inner_n) * kXcd + xcd;
-        g = u / n_tiles;
-        nt = u % n_tiles;
-        inner = q % inner_n;
-        live = u < a.G * n_tiles;
-    }
+    const TileId tile = tile_of_block(a, n_tiles, inner_n);
+    const int g = tile.g, nt = tile.nt, inner = tile.inner;
 
-    // Top-1 combine fused into GEMM-2 leaves rows of dropped tokens unwritten: zero them here,
-    // spread over all work-groups (a dropped token has no other writer).
-    if (EPI == EPI_SCATTER && a.zero_slot_idx) {
-        for (int t = blockIdx.x; t < a.T; t += gridDim.x) {
-            if (a.zero_slot_idx[t] < 0) {
-                uint4* o = reinterpret_cast<uint4*>(a.out + (size_t)t * a.N);
-                for (int i = tid; i < a.N / 8; i += NT) o[i] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    }
-    if (!live) return;
+    if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NT);
+    if (!tile.live) return;
     const int mt = inner % m_tiles, ks = inner / m_tiles;
     const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
     const int m0 = mt * MT;
@@ -183,15 +144,8 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
             af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
-            uint32_t lo[4], hi[4];
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint32_t r0 = dw(src[2 * p], qq), r1 = dw(src[2 * p + 1], qq);
-                lo[p] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);   // column 2qq   : k = 2p, 2p+1
-                hi[p] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // column 2qq+1
-            }
-            const bf16x8_t blo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-            const bf16x8_t bhi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            bf16x8_t blo, bhi;
+            b_frag_pair(src, qq, blo, bhi);
 #pragma unroll
             for (int ms = 0; ms < MSUB; ++ms) {
                 acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
@@ -238,14 +192,10 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
     if (!col_ok) return;
     const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
     float bias[8];
+    if (EPI != EPI_PARTIAL) load_bias8(a, g, n_lane, bias);
+    else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-    if (a.bias && EPI != EPI_PARTIAL) {
-        const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + n_lane);
-        bias[0] = __uint_as_float(bv.x << 16); bias[1] = __uint_as_float(bv.x & 0xffff0000u);
-        bias[2] = __uint_as_float(bv.y << 16); bias[3] = __uint_as_float(bv.y & 0xffff0000u);
-        bias[4] = __uint_as_float(bv.z << 16); bias[5] = __uint_as_float(bv.z & 0xffff0000u);
-        bias[6] = __uint_as_float(bv.w << 16); bias[7] = __uint_as_float(bv.w & 0xffff0000u);
+        for (int i = 0; i < 8; ++i) bias[i] = 0.f;
     }
 #pragma unroll
     for (int ms = 0; ms < MSUB; ++ms) {
@@ -256,41 +206,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
             float v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
-            const long long grow = (long long)g * a.o_group_stride + m0 + rl;   // row in [G, o_group_stride]
-            if (EPI == EPI_PARTIAL) {
-                float* o = a.partial + ((size_t)ks * a.partial_rows + grow) * a.N + n_lane;
-                *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
-                *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
-                continue;
-            }
-            size_t orow = (size_t)grow;
-            if (EPI == EPI_GELU) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = gelu_tanh(v[i]);
-            } else if (EPI == EPI_SCATTER) {
-                const int t = a.scatter_map[(size_t)g * a.scatter_stride + m0 + rl];   // token of this expert row
-                const float gw = a.gate_w[(size_t)t * a.top_k];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] *= gw;
-                orow = (size_t)t;
-            } else if (EPI == EPI_COMBINE) {
-                // dense branch + sum_j keep_j g_j ye[e_j, slot_j, :] for token grow
-                for (int j = 0; j < a.top_k; ++j) {
-                    const int s = a.slot_idx[grow * a.top_k + j];
-                    if (s < 0) continue;
-                    const int e = a.expert_idx[grow * a.top_k + j];
-                    const float gw = a.gate_w[grow * a.top_k + j];
-                    const uint4 yv = *reinterpret_cast<const uint4*>(a.ye + ((size_t)e * a.C + s) * a.N + n_lane);
-                    v[0] = fmaf(gw, __uint_as_float(yv.x << 16), v[0]); v[1] = fmaf(gw, __uint_as_float(yv.x & 0xffff0000u), v[1]);
-                    v[2] = fmaf(gw, __uint_as_float(yv.y << 16), v[2]); v[3] = fmaf(gw, __uint_as_float(yv.y & 0xffff0000u), v[3]);
-                    v[4] = fmaf(gw, __uint_as_float(yv.z << 16), v[4]); v[5] = fmaf(gw, __uint_as_float(yv.z & 0xffff0000u), v[5]);
-                    v[6] = fmaf(gw, __uint_as_float(yv.w << 16), v[6]); v[7] = fmaf(gw, __uint_as_float(yv.w & 0xffff0000u), v[7]);
-                }
-            }
-            uint4 o;
-            o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
-            o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-            *reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane) = o;
+            finish_row<EPI>(a, g, m0 + rl, ks, n_lane, v);
         }
     }
 }
@@ -360,9 +276,7 @@ template <int MT, int NW, int EPI, int NBUF>
 static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
-    const long long per_group = (long long)n_tiles * m_tiles * a.ksplit;
-    const long long blocks = a.G >= kXcd ? (long long)(a.G + kXcd - 1) / kXcd * kXcd * per_group
-                                         : ((long long)a.G * n_tiles + kXcd - 1) / kXcd * kXcd * m_tiles * a.ksplit;
+    const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles * a.ksplit);
     hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a);
 }
 

@@ -1,0 +1,217 @@
+// Tiled bf16 MFMA grouped GEMM for groups with many rows: experts holding more than 64 tokens and
+// the dense branch of Residual-MoE (paper Sec. 4.1.1), where the products are bound by the matrix
+// cores, not by weight traffic.
+//
+// A work-group of 4 waves (2 x 2) owns a (2*WM) x 256 output tile; a wave owns WM x 128 of it.
+// Both operands pass through LDS in 32-deep k-stages, kNS stages deep, filled by direct
+// global->LDS loads (global_load_lds_dwordx4: 16 bytes per lane, a wave writes 1 KB of contiguous
+// LDS per instruction, no staging registers), so kNS-1 stages are always in flight:
+//   * weights: 32 k-rows x 256 columns, K-major exactly as in memory (a wave instruction copies
+//     two 512-byte rows); a wave reads its 128 columns as eight 16-byte row pieces per lane and
+//     turns them into eight MFMA B fragments with the same in-register 8x8 transpose as the
+//     streaming kernel.  Each weight byte is fetched from L2 once per work-group and serves 2*WM rows;
+//   * activations: (2*WM) rows x 64 bytes.  Direct loads leave no room for row padding, so bank
+//     conflicts of the A-fragment reads (16 lanes, 16 rows, same k) are avoided by a swizzle done
+//     on the global side: 16-byte slot `pos` of row r holds k-piece pos ^ ((r >> 2) & 3).
+// The direct loads are issued through inline asm: the compiler then does not know they write LDS
+// and does not put a full vmcnt(0) wait in front of every LDS read; completion is tracked by hand
+// (in-order vmcnt: 8 loads per wave and stage).
+// v_mfma_f32_16x16x32_bf16, fp32 accumulation; epilogues shared with the streaming kernel.
+// Requires K to be a multiple of 32 (no zero fill is possible on the way into LDS).
+#include "ffn_common.h"
+
+namespace moe {
+
+constexpr int kTK = 32;            // k-rows per stage
+constexpr int kTBN = 256;          // tile columns
+constexpr int kTBBytes = kTK * kTBN * 2;   // weight bytes per stage (16 KB)
+
+// 16 bytes per lane from global memory straight into LDS at lds_wave_base + lane*16
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_wave_base) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int WM> struct TileCfg {
+    static constexpr int BM = 2 * WM;
+    static constexpr int A_BYTES = BM * 64;                    // activation bytes per stage
+    static constexpr int STAGE = A_BYTES + kTBBytes;
+    static constexpr int NS = WM == 128 ? 4 : 5;               // stages: 4 x 32 KB or 5 x 24 KB
+    static constexpr int NIA = A_BYTES / 4096;                 // activation loads per wave and stage
+    static constexpr int LDS_BYTES = NS * STAGE + BM * 8;
+};
+
+template <int WM, int EPI>
+__global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
+    typedef TileCfg<WM> Cfg;
+    constexpr int BM = Cfg::BM, MSUB = WM / 16, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE, NS = Cfg::NS;
+    constexpr int NIA = Cfg::NIA, NIB = 4;
+    constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
+
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // NS stages, then BM row indices
+    long long* arow_sh = reinterpret_cast<long long*>(lds + NS * STAGE);
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));   // LDS byte offset of the segment
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c = lane & 15, kg = lane >> 4;
+    const int wm = w >> 1, wn = w & 1;
+
+    const int n_tiles = (a.N + kTBN - 1) / kTBN;
+    const int m_tiles = (a.max_rows + BM - 1) / BM;
+    const TileId tile = tile_of_block(a, n_tiles, m_tiles);
+    const int g = tile.g, nt = tile.nt, mt = tile.inner;
+
+    if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, 256);
+    if (!tile.live) return;
+    const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
+    const int m0 = mt * BM;
+    if (m0 >= rows) return;
+    const int nrows = min(BM, rows - m0);
+
+    for (int i = tid; i < BM; i += 256) {
+        const int r = m0 + min(i, nrows - 1);                   // rows past the end alias the last valid one
+        arow_sh[i] = a.row_map ? (long long)a.row_map[(size_t)g * a.map_stride + r] : (long long)g * a.a_group_stride + r;
+    }
+    __syncthreads();
+
+    // ---- per-lane sources of the direct loads (fixed for the whole k-loop) ---------------------------
+    // activations: wave w, load i copies rows (w*NIA + i)*16 .. +15; lane L -> row +L/4, slot L%4
+    const uint16_t* a_src[NIA];
+#pragma unroll
+    for (int i = 0; i < NIA; ++i) {
+        const int r = (w * NIA + i) * 16 + (lane >> 2);
+        const int kp = (lane & 3) ^ ((r >> 2) & 3);              // swizzle
+        a_src[i] = a.A + (size_t)arow_sh[r] * a.K + kp * 8;
+    }
+    // weights: wave w, load i copies k-rows w*8 + 2i, +1; lane L -> row +L/32, 16-byte column piece L%32
+    const int n0 = nt * kTBN;
+    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * 8 + (lane >> 5)) * a.N +
+                            min(n0 + (lane & 31) * 8, a.N - 8);       // clamped column: loaded, never stored
+    const size_t b_step2 = (size_t)2 * a.N;
+
+    const int steps = a.K / kTK;
+    auto issue = [&](int step) {                                // all loads of one stage, this wave's share
+        const int st = min(step, steps - 1);                    // past the end: harmless re-read, keeps the count uniform
+        const uint32_t base = lds0 + (step % NS) * STAGE;
+        const int k0 = st * kTK;
+#pragma unroll
+        for (int i = 0; i < NIA; ++i)
+            dma16(a_src[i] + k0, __builtin_amdgcn_readfirstlane(base + (w * NIA + i) * 1024));
+        const uint16_t* bp = b_src + (size_t)k0 * a.N;
+#pragma unroll
+        for (int i = 0; i < NIB; ++i)
+            dma16(bp + i * b_step2, __builtin_amdgcn_readfirstlane(base + A_BYTES + (w * NIB + i) * 1024));
+    };
+
+    f32x4_t acc[MSUB][8];
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ ((R >> 2) & 3);
+    // (R >> 2) & 3 == (c >> 2) & 3 because the other terms are multiples of 16
+    const int a_lane = (wm * WM + c) * 64 + ((kg ^ ((c >> 2) & 3)) * 16);
+    const int b_lane = A_BYTES + (kg * 8) * (kTBN * 2) + (wn * 128 + c * 8) * 2;
+
+    auto compute = [&](int buf) {
+        const char* base = lds + buf * STAGE;
+        uint4 braw[8];
+        bf16x8_t af[MSUB];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
+#pragma unroll
+        for (int ms = 0; ms < MSUB; ++ms) af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            bf16x8_t blo, bhi;
+            b_frag_pair(braw, qq, blo, bhi);
+#pragma unroll
+            for (int ms = 0; ms < MSUB; ++ms) {
+                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
+                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop ---------------------------------------------------------------------------------
+    // Before step s: stages s .. s+NS-2 are in flight or landed.  Wait for this wave's share of stage s
+    // (in-order completion: at most (NS-2) stages may stay outstanding), meet the other waves (their
+    // shares have landed too, and nobody still reads the buffer of step s-1), refill that buffer with
+    // stage s+NS-1, multiply stage s.
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s);
+    for (int s = 0; s < steps; ++s) {
+        wait_vmcnt<(NS - 2) * PER_STAGE>();
+        __builtin_amdgcn_s_barrier();
+        issue(s + NS - 1);
+        compute(s % NS);
+    }
+    wait_vmcnt<0>();                      // drain the over-issued tail loads before LDS is released
+
+    // ---- epilogue ------------------------------------------------------------------------------
+    const int n_lane = n0 + wn * 128 + c * 8;
+    if (n_lane >= a.N) return;
+    float bias[8];
+    load_bias8(a, g, n_lane, bias);
+#pragma unroll
+    for (int ms = 0; ms < MSUB; ++ms) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int rl = wm * WM + ms * 16 + kg * 4 + r;       // D: rows 4*(lane/16)+r, column lane%16
+            if (rl >= nrows) continue;
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
+            finish_row<EPI>(a, g, m0 + rl, 0, n_lane, v);
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
+    }
+}
+
+template <int WM, int EPI>
+static int launch_t(const WsGemmArgs& a, hipStream_t s) {
+    constexpr int BM = 2 * WM;
+    const int n_tiles = (a.N + kTBN - 1) / kTBN;
+    const int m_tiles = (a.max_rows + BM - 1) / BM;
+    const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
+    const size_t smem = TileCfg<WM>::LDS_BYTES;
+    static bool attr_set = false;            // one flag per instantiation
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, EPI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((tgemm_kernel<WM, EPI>), dim3((unsigned)blocks), dim3(256), smem, s, a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+template <int EPI>
+static int launch_t_epi(const WsGemmArgs& a, int WM, hipStream_t s) {
+    return WM == 64 ? launch_t<64, EPI>(a, s) : launch_t<128, EPI>(a, s);
+}
+
+// 128 rows per wave (256 x 256 tiles) when that still gives every CU a tile, else 64 (128 x 256)
+int tgemm_wave_rows(int max_rows, int G, int N) {
+    if (max_rows <= 128) return 64;
+    const long long tiles = (long long)G * ((max_rows + 255) / 256) * ((N + kTBN - 1) / kTBN);
+    return tiles >= 256 ? 128 : 64;
+}
+
+bool tgemm_supported(int K, int N) { return K % kTK == 0 && K >= kTK && N % 8 == 0 && N >= 8; }
+
+int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s) {
+    if (a.G <= 0 || a.max_rows <= 0) return MOE_OK;
+    if (a.ksplit != 1 || !tgemm_supported(a.K, a.N)) return MOE_ERR_INVALID_ARG;
+    const int WM = tgemm_wave_rows(a.max_rows, a.G, a.N);
+    switch (epi) {
+        case EPI_STORE: return launch_t_epi<EPI_STORE>(a, WM, s);
+        case EPI_GELU: return launch_t_epi<EPI_GELU>(a, WM, s);
+        case EPI_SCATTER: return launch_t_epi<EPI_SCATTER>(a, WM, s);
+        case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, WM, s);
+        default: return MOE_ERR_INVALID_ARG;
+    }
+}
+
+}  // namespace moe

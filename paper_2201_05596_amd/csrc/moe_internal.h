@@ -136,7 +136,11 @@ struct WsGemmArgs {
 bool wsgemm_supported(int K, int N);
 void wsgemm_pick_tile(int max_rows, int G, int N, int* MT, int* NW);
 int launch_wsgemm(const WsGemmArgs& a, int epi, int MT, int NW, int NBUF, hipStream_t s);
-int wsgemm_chunk_k(int MT);   // k-extent of one LDS chunk = granularity of split-K
+int wsgemm_chunk_k(int MT);
+
+// Tiled variant for groups with many rows (ffn_tile.hip); same arguments, ksplit must be 1.
+int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s);
+bool tgemm_supported(int K, int N);   // K a multiple of 32   // k-extent of one LDS chunk = granularity of split-K
 
 // Sums split-K partials in split order, adds the bias and finishes like EPI_STORE (scatter_map ==
 // nullptr) or EPI_SCATTER (scatter_map given; also zero-fills rows of dropped tokens).
