@@ -2,7 +2,7 @@
 // the dense branch of Residual-MoE (paper Sec. 4.1.1), where the products are bound by the matrix
 // cores, not by weight traffic.
 //
-// A work-group of 4 waves (2 x 2) owns a (2*WM) x 256 output tile; a wave owns WM x 128 of it.
+// A work-group of NWM x 2 waves owns a (NWM*64) x 256 output tile; a wave owns 64 x 128 of it.
 // Both operands pass through LDS in 32-deep k-stages, kNS stages deep, filled by direct
 // global->LDS loads (global_load_lds_dwordx4: 16 bytes per lane, a wave writes 1 KB of contiguous
 // LDS per instruction, no staging registers), so kNS-1 stages are always in flight:
@@ -12,7 +12,7 @@
 //     streaming kernel.  Each weight byte is fetched from L2 once per work-group and serves 2*WM rows;
 //   * activations: (2*WM) rows x 64 bytes.  Direct loads leave no room for row padding, so bank
 //     conflicts of the A-fragment reads (16 lanes, 16 rows, same k) are avoided by a swizzle done
-//     on the global side: 16-byte slot `pos` of row r holds k-piece pos ^ ((r >> 2) & 3).
+//     on the global side: 16-byte slot `pos` of row r holds k-piece pos ^ a_swizzle(r).
 // The direct loads are issued through inline asm: the compiler then does not know they write LDS
 // and does not put a full vmcnt(0) wait in front of every LDS read; completion is tracked by hand
 // (in-order vmcnt: 8 loads per wave and stage).
@@ -30,22 +30,32 @@ constexpr int kTBBytes = kTK * kTBN * 2;   // weight bytes per stage (16 KB)
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_wave_base) : "memory", "m0");
 }
+// A 64-lane 16-byte LDS read is served in four passes of 16 lanes, and the passes are not runs of
+// consecutive lanes: pass 0 takes lanes 0-3, 12-15, 20-23, 24-27, pass 1 lanes 4-7, 8-11, 16-19,
+// 28-31, passes 2 and 3 the same +32.  With rows of 64 bytes a lane (row m, k-group kg) reads 16-byte
+// unit 4*(m%4) + slot, so the four lanes of a pass that share m%4 need four different slots.  Taking
+// slot = kg ^ f(m/4) with f = {0, 2, 3, 1} does that for every pass.
+__device__ __forceinline__ int a_swizzle(int row) { return (0x78 >> (((row >> 2) & 3) * 2)) & 3; }
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int WM> struct TileCfg {
-    static constexpr int BM = 2 * WM;
+// NWM waves along the rows x 2 along the columns; each owns WM rows x 128 columns
+template <int WM, int NWM> struct TileCfg {
+    static constexpr int NWAVES = NWM * 2;
+    static constexpr int BM = NWM * WM;
     static constexpr int A_BYTES = BM * 64;                    // activation bytes per stage
     static constexpr int STAGE = A_BYTES + kTBBytes;
-    static constexpr int NS = WM == 128 ? 4 : 5;               // stages: 4 x 32 KB or 5 x 24 KB
-    static constexpr int NIA = A_BYTES / 4096;                 // activation loads per wave and stage
+    static constexpr int NS = BM == 256 ? 4 : 5;               // stages: 4 x 32 KB or 5 x 24 KB
+    static constexpr int NIA = A_BYTES / 1024 / NWAVES;        // activation loads per wave and stage
+    static constexpr int NIB = kTBBytes / 1024 / NWAVES;       // weight loads per wave and stage
     static constexpr int LDS_BYTES = NS * STAGE + BM * 8;
 };
 
-template <int WM, int EPI>
-__global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
-    typedef TileCfg<WM> Cfg;
+template <int WM, int NWM, int EPI>
+__global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
+    typedef TileCfg<WM, NWM> Cfg;
     constexpr int BM = Cfg::BM, MSUB = WM / 16, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE, NS = Cfg::NS;
-    constexpr int NIA = Cfg::NIA, NIB = 4;
+    constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB, NTHREADS = NWM * 128;
     constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
 
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NS stages, then BM row indices
@@ -61,14 +71,14 @@ __global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
     const TileId tile = tile_of_block(a, n_tiles, m_tiles);
     const int g = tile.g, nt = tile.nt, mt = tile.inner;
 
-    if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, 256);
+    if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NTHREADS);
     if (!tile.live) return;
     const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
     const int m0 = mt * BM;
     if (m0 >= rows) return;
     const int nrows = min(BM, rows - m0);
 
-    for (int i = tid; i < BM; i += 256) {
+    for (int i = tid; i < BM; i += NTHREADS) {
         const int r = m0 + min(i, nrows - 1);                   // rows past the end alias the last valid one
         arow_sh[i] = a.row_map ? (long long)a.row_map[(size_t)g * a.map_stride + r] : (long long)g * a.a_group_stride + r;
     }
@@ -80,12 +90,12 @@ __global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
         const int r = (w * NIA + i) * 16 + (lane >> 2);
-        const int kp = (lane & 3) ^ ((r >> 2) & 3);              // swizzle
+        const int kp = (lane & 3) ^ a_swizzle(r);                 // swizzle
         a_src[i] = a.A + (size_t)arow_sh[r] * a.K + kp * 8;
     }
-    // weights: wave w, load i copies k-rows w*8 + 2i, +1; lane L -> row +L/32, 16-byte column piece L%32
+    // weights: wave w, load i copies k-rows (w*NIB + i)*2, +1; lane L -> row +L/32, 16-byte column piece L%32
     const int n0 = nt * kTBN;
-    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * 8 + (lane >> 5)) * a.N +
+    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * NIB * 2 + (lane >> 5)) * a.N +
                             min(n0 + (lane & 31) * 8, a.N - 8);       // clamped column: loaded, never stored
     const size_t b_step2 = (size_t)2 * a.N;
 
@@ -109,44 +119,61 @@ __global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ ((R >> 2) & 3);
-    // (R >> 2) & 3 == (c >> 2) & 3 because the other terms are multiples of 16
-    const int a_lane = (wm * WM + c) * 64 + ((kg ^ ((c >> 2) & 3)) * 16);
+    // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ a_swizzle(R);
+    // a_swizzle(R) == a_swizzle(c) because the other terms are multiples of 16
+    const int a_lane = (wm * WM + c) * 64 + ((kg ^ a_swizzle(c)) * 16);
     const int b_lane = A_BYTES + (kg * 8) * (kTBN * 2) + (wn * 128 + c * 8) * 2;
 
-    auto compute = [&](int buf) {
-        const char* base = lds + buf * STAGE;
+    // operand fragments of one stage in registers
+    struct Frags {
         uint4 braw[8];
         bf16x8_t af[MSUB];
+    };
+    auto read_frags = [&](Frags& f, int buf) {
+        const char* base = lds + buf * STAGE;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
+        for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
 #pragma unroll
-        for (int ms = 0; ms < MSUB; ++ms) af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
+        for (int ms = 0; ms < MSUB; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
+    };
+    auto mma = [&](const Frags& f) {
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
             bf16x8_t blo, bhi;
-            b_frag_pair(braw, qq, blo, bhi);
+            b_frag_pair(f.braw, qq, blo, bhi);
 #pragma unroll
             for (int ms = 0; ms < MSUB; ++ms) {
-                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
-                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
+                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
+                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
             }
         }
     };
 
     // ---- main loop ---------------------------------------------------------------------------------
-    // Before step s: stages s .. s+NS-2 are in flight or landed.  Wait for this wave's share of stage s
-    // (in-order completion: at most (NS-2) stages may stay outstanding), meet the other waves (their
-    // shares have landed too, and nobody still reads the buffer of step s-1), refill that buffer with
-    // stage s+NS-1, multiply stage s.
+    // In step s the fragments of stage s are already in registers; the step waits for this wave's
+    // share of stage s+1 (in-order completion: NS-3 later stages may stay outstanding), meets the
+    // other waves (their shares have landed too, and nobody reads the buffer of stage s-1 any more),
+    // refills that buffer with stage s+NS-1, then reads the fragments of stage s+1 from LDS while the
+    // matrix cores work on stage s: LDS reads and MFMAs of a wave overlap instead of alternating.
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) issue(s);
-    for (int s = 0; s < steps; ++s) {
-        wait_vmcnt<(NS - 2) * PER_STAGE>();
+    Frags f0, f1;
+    wait_vmcnt<(NS - 2) * PER_STAGE>();
+    __builtin_amdgcn_s_barrier();
+    read_frags(f0, 0);
+    auto step = [&](const Frags& cur, Frags& nxt, int s) {
+        wait_vmcnt<(NS - 3) * PER_STAGE>();
         __builtin_amdgcn_s_barrier();
         issue(s + NS - 1);
-        compute(s % NS);
+        read_frags(nxt, (s + 1) % NS);
+        mma(cur);
+    };
+    int s = 0;
+    for (; s + 2 <= steps; s += 2) {
+        step(f0, f1, s);
+        step(f1, f0, s + 1);
     }
+    if (s < steps) step(f0, f1, s);
     wait_vmcnt<0>();                      // drain the over-issued tail loads before LDS is released
 
     // ---- epilogue ------------------------------------------------------------------------------
@@ -169,27 +196,29 @@ __global__ __launch_bounds__(256) void tgemm_kernel(const WsGemmArgs a) {
     }
 }
 
-template <int WM, int EPI>
+template <int WM, int NWM, int EPI>
 static int launch_t(const WsGemmArgs& a, hipStream_t s) {
-    constexpr int BM = 2 * WM;
+    constexpr int BM = NWM * WM;
     const int n_tiles = (a.N + kTBN - 1) / kTBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
-    const size_t smem = TileCfg<WM>::LDS_BYTES;
+    const size_t smem = TileCfg<WM, NWM>::LDS_BYTES;
     static bool attr_set = false;            // one flag per instantiation
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tgemm_kernel<WM, EPI>), dim3((unsigned)blocks), dim3(256), smem, s, a);
+    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, EPI>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 template <int EPI>
 static int launch_t_epi(const WsGemmArgs& a, int WM, hipStream_t s) {
-    return WM == 64 ? launch_t<64, EPI>(a, s) : launch_t<128, EPI>(a, s);
+    // 128 x 256 tiles: 2 x 2 waves; 256 x 256 tiles: 4 x 2 waves (64 rows per wave keep the accumulators at 128
+    // registers, which the compiler updates in place; 128 rows per wave fill the file and cost copies)
+    return WM == 64 ? launch_t<64, 2, EPI>(a, s) : launch_t<64, 4, EPI>(a, s);
 }
 
 // 128 rows per wave (256 x 256 tiles) when that still gives every CU a tile, else 64 (128 x 256)
