@@ -195,3 +195,22 @@ def test_residual_with_zero_experts_equals_dense_branch():
     h = U.host(inp)
     ref = orc.ffn(h["x"], h["Wd1"], h["bd1"], h["Wd2"], h["bd2"])
     U.assert_close(res["out"], ref, cfg.dtype)
+
+
+# ------------------------------------------------------------------ full sizes, as benchmarked
+
+@pytest.mark.parametrize("name", ["c2", "c3a", "c3b", "c4"])
+def test_layer_full_size(name):
+    """The BASELINE configurations at full size, in the launch configuration bench.py times."""
+    print(f"case full {name}", flush=True)
+    stats = U.check_layer(make_inputs(CONFIGS[name], DEV), lazy_experts=True)
+    print(name, stats, flush=True)
+    assert stats["kept"] > 0
+
+
+def test_layer_full_size_c5_sampled():
+    """Config 5 (17 GB of expert weights): routing in full, outputs on sampled tokens."""
+    print("case full c5 (sampled)", flush=True)
+    stats = U.check_layer_sampled(make_inputs(CONFIGS["c5"], DEV))
+    print("c5", stats, flush=True)
+    assert stats["dropped_tokens"] > 0 and stats["tokens_keeping_all_choices"] > 0
