@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--config", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--capacity-factor", type=float, default=None, help="experiment: override the workload's capacity factor")
+    ap.add_argument("--no-stage-events", action="store_true",
+                    help="experiment: time the steps without the library's per-stage events (no roofline then)")
+    ap.add_argument("--all-stage-events", action="store_true", help="time every stage (more events, slower step)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -113,7 +116,10 @@ def main() -> int:
         layer(inp.x)
     torch.cuda.synchronize()
 
-    moe.moe_profile_enable(args.steps)
+    if not args.no_stage_events:
+        # events only around the two expert GEMMs (the roofline kernel is the longer one): three per step
+        moe.moe_profile_select(None if args.all_stage_events else ["expert_gemm1", "expert_gemm2"])
+        moe.moe_profile_enable(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):

@@ -144,12 +144,16 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
  * kernels' latency as a whole, Sec. 5.4; this splits it per kernel).
  * moe_profile_enable(n > 0) creates events for the next n calls (the one place
  * where the library creates a HIP resource), n = 0 disables and destroys them.
- * While enabled, each moe_layer_forward call records one event on its stream
- * before its first kernel and one after every stage; nothing is read back.
+ * While enabled, each moe_layer_forward call records events on its stream around
+ * the selected stages (one before a stage unless the previous stage just
+ * recorded one, one after it); nothing is read back.  moe_profile_select takes
+ * a bit mask over stage indices (default: all stages); fewer selected stages
+ * mean fewer events and less disturbance of the call being timed.
  * moe_profile_elapsed(call, ms) waits for that call's last event and fills
  * ms[moe_profile_stage_count()] with the milliseconds per stage (0 for stages
  * the call did not run).  Not thread-safe. */
 int moe_profile_enable(int max_calls);
+int moe_profile_select(unsigned stage_mask);
 int moe_profile_calls(void);
 int moe_profile_stage_count(void);
 const char* moe_profile_stage_name(int stage);

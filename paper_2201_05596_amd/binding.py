@@ -21,7 +21,8 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_dispatch",
-                "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_calls",
+                "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
+                "moe_profile_calls",
                 "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
 
 
@@ -67,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_forward.argtypes = [sp] + [vp] * 18 + [vp, st, vp]
     lib.moe_profile_enable.restype = i32
     lib.moe_profile_enable.argtypes = [i32]
+    lib.moe_profile_select.restype = i32
+    lib.moe_profile_select.argtypes = [ctypes.c_uint]
     lib.moe_profile_calls.restype = i32
     lib.moe_profile_calls.argtypes = []
     lib.moe_profile_stage_count.restype = i32
@@ -174,6 +177,13 @@ def moe_layer_forward(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out,
 
 def moe_profile_enable(max_calls: int) -> None:
     _check("moe_profile_enable", load_library().moe_profile_enable(int(max_calls)))
+
+
+def moe_profile_select(stage_names=None) -> None:
+    """Restrict stage timing to the named stages (None = all)."""
+    names = moe_profile_stage_names()
+    mask = 0xFFFFFFFF if stage_names is None else sum(1 << names.index(n) for n in stage_names)
+    _check("moe_profile_select", load_library().moe_profile_select(mask))
 
 
 def moe_profile_calls() -> int:

@@ -17,25 +17,39 @@ const char* const kStageNames[ST_COUNT] = {"gate_logits", "gate_route", "dispatc
                                            "splitk_reduce", "dense_gemm1", "dense_gemm2", "combine"};
 struct Profiler {
     int max_calls = 0, calls = 0, cur = -1;
-    std::vector<hipEvent_t> ev;     // [max_calls][ST_COUNT + 1]
-    std::vector<int> stage;         // stage that ended at each mark (mark 0 = start of the call)
+    unsigned mask = ~0u;            // stages that get their own time
+    bool dirty = false;             // kernels were launched since the last recorded event
+    std::vector<hipEvent_t> ev;     // [max_calls][kMarks]
+    std::vector<int> stage;         // stage that ended at each mark; -1: the mark only opens the next stage
     std::vector<int> nmarks;        // [max_calls]
 } g_prof;
+constexpr int kMarks = 2 * ST_COUNT + 1;
 
+void prof_record(int stage, hipStream_t st) {
+    const int m = g_prof.nmarks[g_prof.cur];
+    if (m >= kMarks) return;
+    g_prof.stage[(size_t)g_prof.cur * kMarks + m] = stage;
+    (void)hipEventRecord(g_prof.ev[(size_t)g_prof.cur * kMarks + m], st);
+    g_prof.nmarks[g_prof.cur] = m + 1;
+    g_prof.dirty = false;
+}
 void prof_begin(hipStream_t st) {
     g_prof.cur = -1;
     if (g_prof.max_calls == 0 || g_prof.calls >= g_prof.max_calls) return;
     g_prof.cur = g_prof.calls++;
-    g_prof.nmarks[g_prof.cur] = 1;
-    (void)hipEventRecord(g_prof.ev[(size_t)g_prof.cur * (ST_COUNT + 1)], st);
+    g_prof.nmarks[g_prof.cur] = 0;
+    g_prof.dirty = true;            // whatever ran before the call
 }
+// before a stage's first launch: open it with an event unless one was just recorded
+void prof_pre(int stage, hipStream_t st) {
+    if (g_prof.cur < 0 || !(g_prof.mask >> stage & 1u)) return;
+    if (g_prof.dirty || g_prof.nmarks[g_prof.cur] == 0) prof_record(-1, st);
+}
+// after a stage's last launch
 void prof_mark(int stage, hipStream_t st) {
     if (g_prof.cur < 0) return;
-    const int m = g_prof.nmarks[g_prof.cur];
-    if (m > ST_COUNT) return;
-    g_prof.stage[(size_t)g_prof.cur * (ST_COUNT + 1) + m] = stage;
-    (void)hipEventRecord(g_prof.ev[(size_t)g_prof.cur * (ST_COUNT + 1) + m], st);
-    g_prof.nmarks[g_prof.cur] = m + 1;
+    if (g_prof.mask >> stage & 1u) prof_record(stage, st);
+    else g_prof.dirty = true;
 }
 
 constexpr size_t kAlign = 256;
@@ -167,6 +181,7 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
+    prof_pre(ST_GEMM1, st);
     const int rc = p.tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
     prof_mark(ST_GEMM1, st);
     return rc;
@@ -183,6 +198,7 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
+    prof_pre(ST_GEMM2, st);
     if (p.ksplit2 == 1) {
         const int epi = scatter ? EPI_SCATTER : EPI_STORE;
         const int rc1 = p.tiled ? launch_tgemm(a, epi, st) : launch_wsgemm(a, epi, p.MT, p.NW2, p.NBUF, st);
@@ -199,6 +215,7 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     r.rows = rows; r.max_rows = s->capacity; r.bias = u16(b2); r.out = u16(dst);
     r.scatter_map = scatter ? slot_token : nullptr; r.gate_w = gate_w; r.top_k = s->top_k;
     r.zero_slot_idx = scatter ? slot_idx : nullptr; r.T = s->T;
+    prof_pre(ST_REDUCE, st);
     rc = launch_splitk_reduce(r, st);
     prof_mark(ST_REDUCE, st);
     return rc;
@@ -216,6 +233,7 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
     const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
                        !tune("MOE_TUNE_NOTILE");
+    prof_pre(ST_DENSE1, st);
     int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
     prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
@@ -223,6 +241,7 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.ye = u16(ye); a.expert_idx = expert_idx; a.slot_idx = slot_idx; a.gate_w = gate_w; a.top_k = s->top_k;
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
+    prof_pre(ST_DENSE2, st);
     rc = tiled ? launch_tgemm(a, EPI_COMBINE, st) : launch_wsgemm(a, EPI_COMBINE, MT, NW, 4, st);
     prof_mark(ST_DENSE2, st);
     return rc;
@@ -352,10 +371,12 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     int32_t* slot_token = slot_token_out ? slot_token_out : at<int32_t>(ws, L.slot_token);
 
     prof_begin(st);
+    prof_pre(ST_LOGITS, st);
     rc = launch_gate_logits(x, dt, Wg, bg, logits, T, d, E, st);
     prof_mark(ST_LOGITS, st);
     if (rc != MOE_OK) return rc;
     int32_t* order = at<int32_t>(ws, L.order);
+    prof_pre(ST_ROUTE, st);
     rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, order,
                       at<int32_t>(ws, L.hist), st);
     prof_mark(ST_ROUTE, st);
@@ -363,21 +384,25 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     const FfnPlan plan = plan_ffn(shape);
     if (!plan.mfma) {
         // fp32 layer: the unfused sequence dispatch -> FFN -> [dense branch] -> combine
+        prof_pre(ST_DISPATCH, st);
         rc = launch_dispatch(x, dt, slot_token, rows, at<void>(ws, L.xe), E, C, d, st);
         prof_mark(ST_DISPATCH, st);
         if (rc != MOE_OK) return rc;
+        prof_pre(ST_GEMM2, st);
         rc = run_ffn_simple(dt, E, C, rows, 0, d, f, at<void>(ws, L.xe), W1, b1, W2, b2, at<void>(ws, L.h),
                             at<void>(ws, L.ye), st);
         prof_mark(ST_GEMM2, st);
         if (rc != MOE_OK) return rc;
         const void* addend = nullptr;
         if (shape->residual) {
+            prof_pre(ST_DENSE2, st);
             rc = run_ffn_simple(dt, 1, T, nullptr, T, d, f, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd),
                                 at<void>(ws, L.dense), st);
             prof_mark(ST_DENSE2, st);
             if (rc != MOE_OK) return rc;
             addend = at<void>(ws, L.dense);
         }
+        prof_pre(ST_COMBINE, st);
         rc = launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, addend, out, T, k, C, d, st);
         prof_mark(ST_COMBINE, st);
         return rc;
@@ -396,6 +421,7 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     if (shape->residual)
         return run_dense_branch(shape, x, Wd1, bd1, Wd2, bd2, at<void>(ws, L.hd), at<void>(ws, L.ye), expert_idx,
                                 slot_idx, gate_w, out, st);
+    prof_pre(ST_COMBINE, st);
     rc = launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, nullptr, out, T, k, C, d, st);
     prof_mark(ST_COMBINE, st);
     return rc;
@@ -407,13 +433,18 @@ int moe_profile_enable(int max_calls) {
     g_prof.max_calls = 0; g_prof.calls = 0; g_prof.cur = -1;
     if (max_calls <= 0) return MOE_OK;
     if (max_calls > 4096) return MOE_ERR_INVALID_ARG;
-    const size_t n = (size_t)max_calls * (ST_COUNT + 1);
+    const size_t n = (size_t)max_calls * kMarks;
     g_prof.ev.resize(n);
     for (size_t i = 0; i < n; ++i)
         if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) { g_prof.ev.resize(i); moe_profile_enable(0); return MOE_ERR_HIP; }
     g_prof.stage.assign(n, -1);
     g_prof.nmarks.assign(max_calls, 0);
     g_prof.max_calls = max_calls;
+    return MOE_OK;
+}
+
+int moe_profile_select(unsigned stage_mask) {
+    g_prof.mask = stage_mask;
     return MOE_OK;
 }
 
@@ -424,14 +455,16 @@ const char* moe_profile_stage_name(int i) { return (i >= 0 && i < ST_COUNT) ? kS
 int moe_profile_elapsed(int call, float* ms) {
     if (!ms || call < 0 || call >= g_prof.calls) return MOE_ERR_INVALID_ARG;
     for (int i = 0; i < ST_COUNT; ++i) ms[i] = 0.f;
-    const size_t base = (size_t)call * (ST_COUNT + 1);
+    const size_t base = (size_t)call * kMarks;
     const int m = g_prof.nmarks[call];
     if (m < 2) return MOE_OK;
     if (hipEventSynchronize(g_prof.ev[base + m - 1]) != hipSuccess) return MOE_ERR_HIP;
     for (int i = 1; i < m; ++i) {
+        const int st = g_prof.stage[base + i];
+        if (st < 0) continue;                  // that event only opened the next stage
         float t = 0.f;
         if (hipEventElapsedTime(&t, g_prof.ev[base + i - 1], g_prof.ev[base + i]) != hipSuccess) return MOE_ERR_HIP;
-        ms[g_prof.stage[base + i]] += t;
+        ms[st] += t;
     }
     return MOE_OK;
 }
