@@ -458,11 +458,19 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 //   second choices: row = total_1[e] + base_2[e] + rank      (all first choices rank first)
 // row >= C -> dropped (-1).  Rows >= expert_rows[e] of slot_token are set to -1.
 // ------------------------------------------------------------------------------------------
-// order[rank] = e, experts ranked by kept rows (most first, ties by index).  The expert GEMMs walk
-// this list round-robin over the XCDs, so every XCD gets the same number of active experts and the
-// long ones start first.  O(E^2) compares, E <= 1024.
+// Launch order of the experts for the grouped GEMMs, which deal consecutive entries round-robin to
+// the 8 XCDs.  Experts are ranked by kept rows (most first, ties by index); active ones are then
+// handed out so that every XCD alternates between a busy expert (matrix-core bound) and a light one
+// (weight-bandwidth bound), neighbouring XCDs in opposite phase: entry p = 8j + x (j-th expert of XCD
+// x) takes the next busiest remaining expert when j + x is even, the next lightest when odd.  All
+// XCDs get the same number of active experts, and while half of them multiply the others stream
+// weights.  Experts without rows follow at the end.  O(E^2) compares, E <= 1024.
+// `sorted` is LDS scratch of E + 1 ints; every thread of the block must call.
 __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */, int E, int32_t* __restrict__ order,
-                                                   int tid, int nthreads) {
+                                                   int32_t* sorted /* LDS */, int tid, int nthreads) {
+    if (tid == 0) sorted[E] = 0;
+    __syncthreads();
+    int active = 0;
     for (int e = tid; e < E; e += nthreads) {
         const int r = rows[e];
         int rank = 0;
@@ -470,20 +478,37 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
             const int ro = rows[o];
             rank += (ro > r || (ro == r && o < e)) ? 1 : 0;
         }
-        order[rank] = e;
+        sorted[rank] = e;
+        active += r > 0 ? 1 : 0;
+    }
+    if (active) atomicAdd(&sorted[E], active);          // integer count in LDS: order-independent
+    __syncthreads();
+    const int na = sorted[E];
+    for (int p = tid; p < E; p += nthreads) {
+        int e;
+        if (p >= na) {
+            e = sorted[p];
+        } else {
+            const int j = p >> 3, x = p & 7;
+            // busy takes among positions 8j .. 8j+x-1: those x' with (j + x') even
+            const int busy_before = 4 * j + ((j & 1) ? (x >> 1) : ((x + 1) >> 1));
+            const int light_before = p - busy_before;
+            e = ((j + x) & 1) ? sorted[na - 1 - light_before] : sorted[busy_before];
+        }
+        order[p] = e;
     }
 }
 
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ expert_rows, int E, int C,
                                                            int32_t* __restrict__ order) {
-    extern __shared__ int32_t smem[];
+    extern __shared__ int32_t smem[];                 // rows [E], sorted [E + 1]
     for (int e = threadIdx.x; e < E; e += 256) smem[e] = min(expert_rows[e], C);
     __syncthreads();
-    write_expert_order(smem, E, order, threadIdx.x, 256);
+    write_expert_order(smem, E, order, smem + E, threadIdx.x, 256);
 }
 
 int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s) {
-    hipLaunchKernelGGL(expert_order_kernel, dim3(1), dim3(256), sizeof(int32_t) * E, s, expert_rows, E, C, order);
+    hipLaunchKernelGGL(expert_order_kernel, dim3(1), dim3(256), sizeof(int32_t) * (2 * E + 1), s, expert_rows, E, C, order);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -564,7 +589,7 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
     }
     if (b == 0) {
         for (int e = tid; e < E; e += kRouteTokens) expert_rows[e] = rows_sh[e];
-        if (expert_order) write_expert_order(rows_sh, E, expert_order, tid, kRouteTokens);
+        if (expert_order) write_expert_order(rows_sh, E, expert_order, part, tid, kRouteTokens);   // part: free by now
     }
 }
 
