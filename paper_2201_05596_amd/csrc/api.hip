@@ -81,26 +81,37 @@ struct FfnPlan {
     int NBUF;           // weight super-fragments kept in flight per wave, plus one
 };
 
-// developer tuning knobs (environment), 0 = not set
-int tune(const char* name) {
-    const char* v = std::getenv(name);
-    return v ? std::atoi(v) : 0;
+// developer tuning knobs (environment, read once), 0 = not set
+enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_COUNT };
+int tune(Knob k) {
+    static const char* const names[KN_COUNT] = {"MOE_TUNE_NBUF", "MOE_TUNE_MT", "MOE_TUNE_NW1", "MOE_TUNE_NW2",
+                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE"};
+    static int values[KN_COUNT];
+    static bool read = false;
+    if (!read) {
+        for (int i = 0; i < KN_COUNT; ++i) {
+            const char* v = std::getenv(names[i]);
+            values[i] = v ? std::atoi(v) : 0;
+        }
+        read = true;
+    }
+    return values[k];
 }
 
 FfnPlan plan_ffn(const moe_shape_t* s) {
     FfnPlan p{};
     p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
     p.ksplit2 = 1;
-    p.NBUF = tune("MOE_TUNE_NBUF") ? tune("MOE_TUNE_NBUF") : 4;
+    p.NBUF = tune(KN_NBUF) ? tune(KN_NBUF) : 4;
     if (!p.mfma) return p;
     p.tiled = s->capacity > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
-              !tune("MOE_TUNE_NOTILE");
+              !tune(KN_NOTILE);
     wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
     int mt2;
     wsgemm_pick_tile(s->capacity, s->E, s->d_model, &mt2, &p.NW2);
-    if (tune("MOE_TUNE_MT")) p.MT = tune("MOE_TUNE_MT");
-    if (tune("MOE_TUNE_NW1")) p.NW1 = tune("MOE_TUNE_NW1");
-    if (tune("MOE_TUNE_NW2")) p.NW2 = tune("MOE_TUNE_NW2");
+    if (tune(KN_MT)) p.MT = tune(KN_MT);
+    if (tune(KN_NW1)) p.NW1 = tune(KN_NW1);
+    if (tune(KN_NW2)) p.NW2 = tune(KN_NW2);
     // GEMM-2 has few output columns; when that leaves the chip short of waves, split K
     const long long touched = s->E < (long long)s->T * s->top_k ? s->E : (long long)s->T * s->top_k;
     const long long m_tiles = (s->capacity + p.MT - 1) / p.MT;
@@ -112,9 +123,9 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
         if (ks > chunks) ks = chunks;
         p.ksplit2 = (int)(ks < 1 ? 1 : ks);
     }
-    if (tune("MOE_TUNE_KSPLIT")) {
+    if (tune(KN_KSPLIT)) {
         const int chunks = (s->d_ffn + wsgemm_chunk_k(p.MT) - 1) / wsgemm_chunk_k(p.MT);
-        p.ksplit2 = tune("MOE_TUNE_KSPLIT") < chunks ? tune("MOE_TUNE_KSPLIT") : chunks;
+        p.ksplit2 = tune(KN_KSPLIT) < chunks ? tune(KN_KSPLIT) : chunks;
     }
     return p;
 }
@@ -232,7 +243,7 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
     const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
-                       !tune("MOE_TUNE_NOTILE");
+                       !tune(KN_NOTILE);
     prof_pre(ST_DENSE1, st);
     int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
     prof_mark(ST_DENSE1, st);

@@ -109,7 +109,8 @@ def test_dispatch_exact_and_combine(dtype, T, d, E, k, C):
 
 @pytest.mark.parametrize("dtype,d,f,E,C,bias", [("f32", 64, 256, 8, 32, True), ("bf16", 256, 1024, 6, 70, True),
                                                 ("bf16", 1024, 4096, 4, 64, False), ("bf16", 2048, 8192, 6, 1, True),
-                                                ("bf16", 264, 520, 3, 130, True)])
+                                                ("bf16", 264, 520, 3, 130, True), ("bf16", 288, 544, 9, 300, True),
+                                                ("bf16", 512, 96, 8, 100, False)])
 def test_expert_ffn(dtype, d, f, E, C, bias):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
@@ -214,3 +215,34 @@ def test_layer_full_size_c5_sampled():
     stats = U.check_layer_sampled(make_inputs(CONFIGS["c5"], DEV))
     print("c5", stats, flush=True)
     assert stats["dropped_tokens"] > 0 and stats["tokens_keeping_all_choices"] > 0
+
+
+def test_stage_timing_api():
+    """moe_profile_*: events around selected stages of moe_layer_forward give positive times."""
+    m = U.amd()
+    inp = make_inputs(REDUCED["c2r"], DEV)
+    cfg = inp.cfg
+    layer = m.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, cfg.capacity, cfg.dtype, inp.Wg, inp.bg, inp.W1,
+                       inp.b1, inp.W2, inp.b2)
+    names = m.moe_profile_stage_names()
+    try:
+        m.moe_profile_select(None)
+        m.moe_profile_enable(3)
+        for _ in range(4):                       # one call more than there are slots: silently untimed
+            layer(inp.x)
+        torch.cuda.synchronize()
+        assert m.moe_profile_calls() == 3
+        ms = dict(zip(names, m.moe_profile_elapsed(2)))
+        for n in ("gate_logits", "gate_route", "expert_gemm1", "expert_gemm2"):
+            assert 0.0 < ms[n] < 50.0, (n, ms)
+        assert ms["dense_gemm1"] == 0.0
+        m.moe_profile_enable(0)
+        m.moe_profile_select(["expert_gemm1"])
+        m.moe_profile_enable(1)
+        layer(inp.x)
+        torch.cuda.synchronize()
+        ms = dict(zip(names, m.moe_profile_elapsed(0)))
+        assert ms["expert_gemm1"] > 0.0 and ms["expert_gemm2"] == 0.0 and ms["gate_logits"] == 0.0
+    finally:
+        m.moe_profile_enable(0)
+        m.moe_profile_select(None)
