@@ -19,6 +19,7 @@
 // v_mfma_f32_16x16x32_bf16, fp32 accumulation; epilogues shared with the streaming kernel.
 // Requires K to be a multiple of 32 (no zero fill is possible on the way into LDS).
 #include "ffn_common.h"
+#include <type_traits>
 
 namespace moe {
 
@@ -113,9 +114,17 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
             dma16(bp + i * b_step2, __builtin_amdgcn_readfirstlane(base + A_BYTES + (w * NIB + i) * 1024));
     };
 
-    f32x4_t acc[MSUB][8];
+    // The rest of the kernel exists once per number ACT of 16-row sub-tiles that a wave works on:
+    // a tile of a lightly loaded expert is pure weight streaming and must not pay matrix-core time
+    // (or LDS reads) for rows that do not exist.  The choice is wave-uniform; a wave without valid rows
+    // still takes part in the loads and barriers.  Separate copies (not branches inside one loop) keep
+    // the accumulators of each copy in place in the register file.
+    const int nsub = __builtin_amdgcn_readfirstlane((min(nrows - wm * WM, WM) + 15) / 16);
+    auto run = [&](auto act_c) {
+    constexpr int ACT = decltype(act_c)::value;
+    f32x4_t acc[ACT][8];
 #pragma unroll
-    for (int i = 0; i < MSUB; ++i)
+    for (int i = 0; i < ACT; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -127,14 +136,14 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
     // operand fragments of one stage in registers
     struct Frags {
         uint4 braw[8];
-        bf16x8_t af[MSUB];
+        bf16x8_t af[ACT];
     };
     auto read_frags = [&](Frags& f, int buf) {
         const char* base = lds + buf * STAGE;
 #pragma unroll
         for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
 #pragma unroll
-        for (int ms = 0; ms < MSUB; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
+        for (int ms = 0; ms < ACT; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
     };
     auto mma = [&](const Frags& f) {
 #pragma unroll
@@ -142,7 +151,7 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
             bf16x8_t blo, bhi;
             b_frag_pair(f.braw, qq, blo, bhi);
 #pragma unroll
-            for (int ms = 0; ms < MSUB; ++ms) {
+            for (int ms = 0; ms < ACT; ++ms) {
                 acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
                 acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
             }
@@ -178,11 +187,11 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
 
     // ---- epilogue ------------------------------------------------------------------------------
     const int n_lane = n0 + wn * 128 + c * 8;
-    if (n_lane >= a.N) return;
+        if (n_lane >= a.N) return;
     float bias[8];
     load_bias8(a, g, n_lane, bias);
 #pragma unroll
-    for (int ms = 0; ms < MSUB; ++ms) {
+    for (int ms = 0; ms < ACT; ++ms) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int rl = wm * WM + ms * 16 + kg * 4 + r;       // D: rows 4*(lane/16)+r, column lane%16
@@ -194,6 +203,10 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
     }
+    };
+    if (nsub > 2) run(std::integral_constant<int, MSUB>());
+    else if (nsub == 2) run(std::integral_constant<int, 2>());
+    else run(std::integral_constant<int, 1>());
 }
 
 template <int WM, int NWM, int EPI>
