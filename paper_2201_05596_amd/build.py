@@ -22,6 +22,7 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    *os.environ.get("MOE_HIPCC_EXTRA", "").split(),      # developer experiments (-D...)
 ]
 
 

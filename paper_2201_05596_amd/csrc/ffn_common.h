@@ -41,10 +41,10 @@ struct TileId {
     int g, nt, inner;
     bool live;
 };
-__device__ __forceinline__ TileId tile_of_block(const WsGemmArgs& a, int n_tiles, int inner_n) {
+__device__ __forceinline__ TileId tile_of_block(const WsGemmArgs& a, int n_tiles, int inner_n, int block) {
     TileId t;
-    const int xcd = blockIdx.x % kXcd;
-    const int q = blockIdx.x / kXcd;
+    const int xcd = block % kXcd;
+    const int q = block / kXcd;
     if (a.G >= kXcd) {
         const int per_group = n_tiles * inner_n;
         const int slot = (q / per_group) * kXcd + xcd;
@@ -89,21 +89,43 @@ __device__ __forceinline__ void zero_dropped_rows(const WsGemmArgs& a, int tid, 
     }
 }
 
+// 16-byte loads and stores with the non-temporal hint: data that passes through once (expert weights at a
+// few rows per expert, results nobody reads soon) should not push reusable lines out of the caches.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream16(void* p, const uint4 o) {
+    const u32x4_t v = {o.x, o.y, o.z, o.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+}
+
+// 8 bf16 biases of columns n_lane.. as loaded (zero without a bias vector), and their fp32 values
+__device__ __forceinline__ uint4 load_bias_raw(const WsGemmArgs& a, int g, int n_lane) {
+    return a.bias ? *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + n_lane) : make_uint4(0, 0, 0, 0);
+}
+__device__ __forceinline__ void unpack_bias8(const uint4 bv, float (&bias)[8]) {
+    bias[0] = __uint_as_float(bv.x << 16); bias[1] = __uint_as_float(bv.x & 0xffff0000u);
+    bias[2] = __uint_as_float(bv.y << 16); bias[3] = __uint_as_float(bv.y & 0xffff0000u);
+    bias[4] = __uint_as_float(bv.z << 16); bias[5] = __uint_as_float(bv.z & 0xffff0000u);
+    bias[6] = __uint_as_float(bv.w << 16); bias[7] = __uint_as_float(bv.w & 0xffff0000u);
+}
 __device__ __forceinline__ void load_bias8(const WsGemmArgs& a, int g, int n_lane, float (&bias)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-    if (a.bias) {
-        const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + n_lane);
-        bias[0] = __uint_as_float(bv.x << 16); bias[1] = __uint_as_float(bv.x & 0xffff0000u);
-        bias[2] = __uint_as_float(bv.y << 16); bias[3] = __uint_as_float(bv.y & 0xffff0000u);
-        bias[4] = __uint_as_float(bv.z << 16); bias[5] = __uint_as_float(bv.z & 0xffff0000u);
-        bias[6] = __uint_as_float(bv.w << 16); bias[7] = __uint_as_float(bv.w & 0xffff0000u);
-    }
+    unpack_bias8(load_bias_raw(a, g, n_lane), bias);
+}
+
+// Token and gate probability of expert row `row` of group g (top-1 combine fused into GEMM-2)
+__device__ __forceinline__ void scatter_lookup(const WsGemmArgs& a, int g, int row, int& t, float& gw) {
+    t = a.scatter_map[(size_t)g * a.scatter_stride + row];
+    gw = a.gate_w[(size_t)t * a.top_k];
 }
 
 // Finishes 8 consecutive columns n_lane.. of row `row` (index inside group g): v = acc + bias on entry.
+// EPI_SCATTER: (t, gw) = scatter_lookup of the row, fetched by the caller.
 template <int EPI>
-__device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, int ks, int n_lane, float (&v)[8]) {
+__device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, int ks, int n_lane, float (&v)[8],
+                                           int t = 0, float gw = 1.f) {
     const long long grow = (long long)g * a.o_group_stride + row;   // row in [G, o_group_stride]
     if (EPI == EPI_PARTIAL) {
         float* o = a.partial + ((size_t)ks * a.partial_rows + grow) * a.N + n_lane;
@@ -116,8 +138,6 @@ __device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, 
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = gelu_tanh(v[i]);
     } else if (EPI == EPI_SCATTER) {
-        const int t = a.scatter_map[(size_t)g * a.scatter_stride + row];   // token of this expert row
-        const float gw = a.gate_w[(size_t)t * a.top_k];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] *= gw;
         orow = (size_t)t;
@@ -138,7 +158,11 @@ __device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, 
     uint4 o;
     o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
     o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-    *reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane) = o;
+    // h and the layer output are written once and read much later or never: streaming stores keep them
+    // from displacing the activation rows in L2.  Expert outputs and split-K partials are read back at once.
+    uint4* dst = reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane);
+    if (EPI == EPI_STORE) *dst = o;
+    else store_stream16(dst, o);
 }
 
 }  // namespace moe

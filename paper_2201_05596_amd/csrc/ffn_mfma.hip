@@ -34,8 +34,13 @@ constexpr int kSF = 32;             // k-rows per super-fragment (one 16x16x32 M
 constexpr int kWaveCols = 128;      // output columns per wave
 constexpr int kLdsTileElems = 8192; // MT * KC: bf16 elements of one LDS activation buffer
 
+// One tile of work: virtual block vb computes rows m0.. of group g, column tile nt, k-split ks.
+struct WsWork {
+    int vb, g, nt, m0, nrows, ch_beg, ch_end;
+};
+
 template <int MT, int NW, int EPI, int NBUF>
-__global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
+__global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, const int total_blocks) {
     constexpr int NT = NW * 64;
     constexpr int MSUB = MT / 16;
     constexpr int KC = kLdsTileElems / MT;        // k-extent of one LDS chunk
@@ -47,167 +52,205 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a) {
 
     __shared__ __attribute__((aligned(16))) char lds[2 * MT * STRIDE];
     __shared__ long long arow_sh[MT];
+    __shared__ int tok_sh[MT];                     // EPI_SCATTER: token and gate probability of the tile's rows
+    __shared__ float gw_sh[MT];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int c = lane & 15, kg = lane >> 4;
 
-    // ---- which tile ------------------------------------------------------------------
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
     const int inner_n = m_tiles * a.ksplit;
-    const TileId tile = tile_of_block(a, n_tiles, inner_n);
-    const int g = tile.g, nt = tile.nt, inner = tile.inner;
+    const int chunks_total = (a.K + KC - 1) / KC;
+    const int chunks_per = (chunks_total + a.ksplit - 1) / a.ksplit;     // whole chunks per k-split
 
     if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NT);
-    if (!tile.live) return;
-    const int mt = inner % m_tiles, ks = inner / m_tiles;
-    const int rows = a.rows ? min(a.rows[g], a.max_rows) : a.fixed_rows;
-    const int m0 = mt * MT;
-    if (m0 >= rows) return;
-    const int nrows = min(MT, rows - m0);
 
-    // ---- k range of this split (whole chunks) --------------------------------------------
-    const int chunks_total = (a.K + KC - 1) / KC;
-    const int chunks_per = (chunks_total + a.ksplit - 1) / a.ksplit;
-    const int ch_beg = ks * chunks_per;
-    const int ch_end = min(ch_beg + chunks_per, chunks_total);
-    if (ch_beg >= ch_end && EPI != EPI_PARTIAL) return;
-
-    // ---- A rows of the tile ----------------------------------------------------------
-    if (tid < MT) {
-        const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
-        long long ar;
-        if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
-        else ar = (long long)g * a.a_group_stride + r;
-        arow_sh[tid] = ar;
-    }
-    __syncthreads();
-
-    // ---- per-lane weight pointer: 8 columns n_lane..n_lane+7 of rows k ------------------------
-    const int n_lane_raw = nt * (NW * kWaveCols) + w * kWaveCols + c * 8;
-    const bool col_ok = n_lane_raw < a.N;
-    const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
-    const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
-
-    f32x4_t acc[MSUB][8];
-#pragma unroll
-    for (int i = 0; i < MSUB; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    // activation chunk: global -> registers -> LDS.  Each thread moves NP 16-byte pieces per chunk;
-    // their rows and k-offsets never change, so the row pointers are formed once.  The loads are
-    // unconditional (k clamped into the row, the value replaced by zero past K) so that the main
-    // loop has no branches around memory operations and the prefetches really stay in flight.
-    const uint16_t* arow_ptr[NP];
-    int akp[NP];
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-        const int p = tid + i * NT;
-        arow_ptr[i] = a.A + (size_t)arow_sh[p / (KC / 8)] * a.K;
-        akp[i] = (p % (KC / 8)) * 8;
-    }
-    uint4 areg[NP];
-    auto a_load = [&](int ch) {                     // loads only: nothing here waits for them
-        const int k0 = ch * KC;
-#pragma unroll
-        for (int i = 0; i < NP; ++i)
-            areg[i] = *reinterpret_cast<const uint4*>(arow_ptr[i] + min(k0 + akp[i], a.K - 8));
-    };
-    auto a_store = [&](int ch, int buf) {           // zero past K, then registers -> LDS
-        char* base = lds + buf * MT * STRIDE;
-        const int k0 = ch * KC;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int p = tid + i * NT;
-            const int r = p / (KC / 8), kp = p % (KC / 8);
-            const bool in = k0 + akp[i] < a.K;
-            const uint4 v = areg[i];
-            *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) =
-                make_uint4(in ? v.x : 0u, in ? v.y : 0u, in ? v.z : 0u, in ? v.w : 0u);
+    // ---- the work-group's tiles ---------------------------------------------------------------
+    // The grid holds as many work-groups as fit on the chip at once; work-group b takes the virtual
+    // blocks b, b + gridDim.x, ... that have work (the XCD of a virtual block is that of b: the grid
+    // is a multiple of the XCD count).  Knowing the next tile early lets the weight stream run on
+    // across tile boundaries.  Everything here is uniform over the work-group.
+    auto find_work = [&](int vb) {
+        WsWork t{};
+        for (; vb < total_blocks; vb += gridDim.x) {
+            const TileId tile = tile_of_block(a, n_tiles, inner_n, vb);
+            if (!tile.live) continue;
+            const int rows = a.rows ? min(a.rows[tile.g], a.max_rows) : a.fixed_rows;
+            const int mt = tile.inner % m_tiles, ks = tile.inner / m_tiles;
+            if (mt * MT >= rows) continue;
+            t.ch_beg = ks * chunks_per;
+            t.ch_end = min(t.ch_beg + chunks_per, chunks_total);
+            if (t.ch_beg >= t.ch_end && EPI != EPI_PARTIAL) continue;
+            t.g = tile.g; t.nt = tile.nt; t.m0 = mt * MT; t.nrows = min(MT, rows - t.m0);
+            break;
         }
+        t.vb = vb;
+        return t;
     };
+    // first of the 8 columns of this lane in column tile nt, and whether they exist
+    auto lane_col = [&](int nt) { return nt * (NW * kWaveCols) + w * kWaveCols + c * 8; };
 
-    // weight super-fragment: rows k0 + kg*8 + j, j = 0..7 (clamped to the last row; A is zero there)
-    uint4 raw[NBUF][8];
-    auto b_load = [&](uint4 (&dst)[8], int k0) {
-        // K is a multiple of 8: a lane's 8 rows are all inside or all outside; outside ones re-read
-        // the last 8 rows (in bounds) and meet zeros on the activation side
-        const uint16_t* p = Bg + (size_t)min(k0 + kg * 8, a.K - 8) * a.N;
+    int akp[NP];                                   // k-offset of this thread's activation pieces
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dst[j] = *reinterpret_cast<const uint4*>(p + (size_t)j * a.N);
-    };
-    auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
-        bf16x8_t af[MSUB];
-#pragma unroll
-        for (int ms = 0; ms < MSUB; ++ms)
-            af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
-#pragma unroll
-        for (int qq = 0; qq < 4; ++qq) {
-            bf16x8_t blo, bhi;
-            b_frag_pair(src, qq, blo, bhi);
-#pragma unroll
-            for (int ms = 0; ms < MSUB; ++ms) {
-                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
-                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
-            }
+    for (int i = 0; i < NP; ++i) akp[i] = ((tid + i * NT) % (KC / 8)) * 8;
+
+    uint4 raw[NBUF][8];                            // weight super-fragments in flight
+    bool primed = false;                           // raw[0..NBUF-2] already hold this tile's first fragments
+
+    WsWork cur = find_work(blockIdx.x);
+    while (cur.vb < total_blocks) {
+        const WsWork nxt = find_work(cur.vb + gridDim.x);
+        const bool has_next = nxt.vb < total_blocks;
+        const int g = cur.g, m0 = cur.m0, nrows = cur.nrows, ch_beg = cur.ch_beg, ch_end = cur.ch_end;
+
+        // ---- A rows of the tile ----------------------------------------------------------
+        lds_barrier();                                              // the previous tile's readers are done
+        if (tid < MT) {
+            const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
+            long long ar;
+            if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
+            else ar = (long long)g * a.a_group_stride + r;
+            arow_sh[tid] = ar;
+            if (EPI == EPI_SCATTER) scatter_lookup(a, g, r, tok_sh[tid], gw_sh[tid]);
         }
-    };
-
-    if (ch_beg < ch_end) {
-        // prologue: first weight super-fragments in flight, first activation chunk in LDS
-#pragma unroll
-        for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
-        a_load(ch_beg);
-        a_store(ch_beg, 0);
         lds_barrier();
 
-        const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
-        for (int ch = ch_beg; ch < ch_end; ++ch) {
-            const int buf = (ch - ch_beg) & 1;
-            a_load(ch + 1);                    // next chunk (past the end: clamped and zeroed, never used)
-            __builtin_amdgcn_sched_barrier(0);
-            const char* a_lane = a_lane0 + buf * MT * STRIDE;
-            const int kbase = ch * KC;
+        // ---- per-lane weight pointers: 8 columns n_lane..n_lane+7 of rows k, this tile and the next ----
+        const int n_lane_raw = lane_col(cur.nt);
+        const bool col_ok = n_lane_raw < a.N;
+        const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
+        const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
+        // everything the epilogue needs from memory is fetched here: a load issued after the weight
+        // fragments that run ahead into the next tile could only be waited for together with them
+        const uint4 bias_raw = EPI != EPI_PARTIAL ? load_bias_raw(a, g, n_lane) : make_uint4(0, 0, 0, 0);
+        const uint16_t* Bn = a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
+        const int k_end_pad = ch_end * KC;                          // first k that belongs to the next tile
+        const int k_next = has_next ? nxt.ch_beg * KC : 0;
+
+        f32x4_t acc[MSUB][8];
 #pragma unroll
-            for (int s = 0; s < SFC; s += NBUF) {
+        for (int i = 0; i < MSUB; ++i)
 #pragma unroll
-                for (int b = 0; b < NBUF; ++b) {
-                    // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b.
-                    // Unconditional: past the last row the loads re-read the last rows and are dropped.
-                    // The scheduling barriers pin that order: left alone, the compiler sinks the loads
-                    // down to their first use and the prefetch distance collapses to zero.
-                    b_load(raw[(b + NBUF - 1) % NBUF], kbase + (s + b + NBUF - 1) * kSF);
-                    __builtin_amdgcn_sched_barrier(0);
-                    sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        // activation chunk: global -> registers -> LDS.  Each thread moves NP 16-byte pieces per chunk;
+        // their rows and k-offsets never change, so the row pointers are formed once.  The loads are
+        // unconditional (k clamped into the row, the value replaced by zero past K) so that the main
+        // loop has no branches around memory operations and the prefetches really stay in flight.
+        const uint16_t* arow_ptr[NP];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) arow_ptr[i] = a.A + (size_t)arow_sh[(tid + i * NT) / (KC / 8)] * a.K;
+        uint4 areg[NP];
+        auto a_load = [&](int ch) {                     // loads only: nothing here waits for them
+            const int k0 = ch * KC;
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                areg[i] = *reinterpret_cast<const uint4*>(arow_ptr[i] + min(k0 + akp[i], a.K - 8));
+        };
+        auto a_store = [&](int ch, int buf) {           // zero past K, then registers -> LDS
+            char* base = lds + buf * MT * STRIDE;
+            const int k0 = ch * KC;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int p = tid + i * NT;
+                const int r = p / (KC / 8), kp = p % (KC / 8);
+                const bool in = k0 + akp[i] < a.K;
+                const uint4 v = areg[i];
+                *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) =
+                    make_uint4(in ? v.x : 0u, in ? v.y : 0u, in ? v.z : 0u, in ? v.w : 0u);
+            }
+        };
+
+        // weight super-fragment: rows k0 + kg*8 + j, j = 0..7.  K is a multiple of 8: a lane's 8 rows are all
+        // inside or all outside.  Rows in [K, k_end_pad) re-read the last 8 rows (in bounds) and meet zeros on
+        // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
+        // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
+        // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
+        auto b_load = [&](uint4 (&dst)[8], int k0) {
+            const int kk = k0 + kg * 8;
+            const bool own = kk < k_end_pad;
+            const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
+        };
+        auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
+            bf16x8_t af[MSUB];
+#pragma unroll
+            for (int ms = 0; ms < MSUB; ++ms)
+                af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                bf16x8_t blo, bhi;
+                b_frag_pair(src, qq, blo, bhi);
+#pragma unroll
+                for (int ms = 0; ms < MSUB; ++ms) {
+                    acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
+                    acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
                 }
             }
-            a_store(ch + 1, buf ^ 1);
-            lds_barrier();
-        }
-    }
+        };
 
-    // ---- epilogue ------------------------------------------------------------------------
-    if (!col_ok) return;
-    const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
-    float bias[8];
-    if (EPI != EPI_PARTIAL) load_bias8(a, g, n_lane, bias);
-    else {
+        if (ch_beg < ch_end) {
+            // prologue: first weight super-fragments in flight (unless the previous tile already
+            // fetched them), first activation chunk in LDS
+            if (!primed) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-    }
+                for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
+            }
+            a_load(ch_beg);
+            a_store(ch_beg, 0);
+            lds_barrier();
+
+            const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
+            for (int ch = ch_beg; ch < ch_end; ++ch) {
+                const int buf = (ch - ch_beg) & 1;
+                a_load(ch + 1);                    // next chunk (past the end: clamped and zeroed, never used)
+                __builtin_amdgcn_sched_barrier(0);
+                const char* a_lane = a_lane0 + buf * MT * STRIDE;
+                const int kbase = ch * KC;
 #pragma unroll
-    for (int ms = 0; ms < MSUB; ++ms) {
+                for (int s = 0; s < SFC; s += NBUF) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int rl = ms * 16 + mg * 4 + r;
-            if (rl >= nrows) continue;
-            float v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
-            finish_row<EPI>(a, g, m0 + rl, ks, n_lane, v);
+                    for (int b = 0; b < NBUF; ++b) {
+                        // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b.
+                        // The scheduling barriers pin that order: left alone, the compiler sinks the loads
+                        // down to their first use and the prefetch distance collapses to zero.
+                        b_load(raw[(b + NBUF - 1) % NBUF], kbase + (s + b + NBUF - 1) * kSF);
+                        __builtin_amdgcn_sched_barrier(0);
+                        sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                a_store(ch + 1, buf ^ 1);
+                lds_barrier();
+            }
+            primed = has_next;
+        } else {
+            primed = false;
         }
+
+        // ---- epilogue ------------------------------------------------------------------------
+        if (col_ok) {
+            const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
+            const int ks = ch_beg / chunks_per;
+            float bias[8];
+            unpack_bias8(bias_raw, bias);
+#pragma unroll
+            for (int ms = 0; ms < MSUB; ++ms) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int rl = ms * 16 + mg * 4 + r;
+                    if (rl >= nrows) continue;
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
+                    finish_row<EPI>(a, g, m0 + rl, ks, n_lane, v, EPI == EPI_SCATTER ? tok_sh[rl] : 0,
+                                    EPI == EPI_SCATTER ? gw_sh[rl] : 1.f);
+                }
+            }
+        }
+        cur = nxt;
     }
 }
 
@@ -272,17 +315,31 @@ int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
+// work-groups of `kernel` that fit on the chip at once (a multiple of the XCD count), cached by the caller
+static int resident_blocks(const void* kernel, int threads) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kXcd)
+        cus = 256;
+    return per_cu * cus / kXcd * kXcd;
+}
+
 template <int MT, int NW, int EPI, int NBUF>
-static void launch_cfg(const WsGemmArgs& a, hipStream_t s) {
+static bool launch_cfg(const WsGemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
-    const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles * a.ksplit);
-    hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a);
+    const long long total = tile_grid_blocks(a, n_tiles, m_tiles * a.ksplit);      // a multiple of the XCD count
+    if (total > (1ll << 30)) return false;
+    static int resident = 0;                                                       // one per instantiation
+    if (!resident) resident = resident_blocks(reinterpret_cast<const void*>(&wsgemm_kernel<MT, NW, EPI, NBUF>), NW * 64);
+    const long long blocks = total < resident ? total : resident;
+    hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a, (int)total);
+    return true;
 }
 
 template <int EPI>
 static bool launch_epi(const WsGemmArgs& a, int MT, int NW, int NBUF, hipStream_t s) {
-#define MOE_WS_CASE(mt, nw, nb) if (MT == mt && NW == nw && NBUF == nb) { launch_cfg<mt, nw, EPI, nb>(a, s); return true; }
+#define MOE_WS_CASE(mt, nw, nb) if (MT == mt && NW == nw && NBUF == nb) return launch_cfg<mt, nw, EPI, nb>(a, s);
     MOE_WS_CASE(16, 4, 2) MOE_WS_CASE(16, 2, 2) MOE_WS_CASE(32, 4, 2) MOE_WS_CASE(32, 2, 2)
     MOE_WS_CASE(64, 4, 2) MOE_WS_CASE(64, 2, 2)
     MOE_WS_CASE(16, 4, 4) MOE_WS_CASE(16, 2, 4) MOE_WS_CASE(32, 4, 4) MOE_WS_CASE(32, 2, 4)

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
 
     const int n_tiles = (a.N + kTBN - 1) / kTBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
-    const TileId tile = tile_of_block(a, n_tiles, m_tiles);
+    const TileId tile = tile_of_block(a, n_tiles, m_tiles, blockIdx.x);
     const int g = tile.g, nt = tile.nt, mt = tile.inner;
 
     if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NTHREADS);
@@ -199,7 +199,10 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
             float v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
-            finish_row<EPI>(a, g, m0 + rl, 0, n_lane, v);
+            int t = 0;
+            float gw = 1.f;
+            if (EPI == EPI_SCATTER) scatter_lookup(a, g, m0 + rl, t, gw);
+            finish_row<EPI>(a, g, m0 + rl, 0, n_lane, v, t, gw);
         }
         __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
     }
