@@ -82,10 +82,10 @@ struct FfnPlan {
 };
 
 // developer tuning knobs (environment, read once), 0 = not set
-enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_COUNT };
+enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_COUNT };
 int tune(Knob k) {
     static const char* const names[KN_COUNT] = {"MOE_TUNE_NBUF", "MOE_TUNE_MT", "MOE_TUNE_NW1", "MOE_TUNE_NW2",
-                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE"};
+                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE", "MOE_TUNE_F32GATE"};
     static int values[KN_COUNT];
     static bool read = false;
     if (!read) {
@@ -132,7 +132,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
 
 // Carving of the caller's workspace.  Offsets in bytes; every region 256-byte aligned.
 struct WsLayout {
-    size_t logits, hist, expert_idx, slot_idx, gate_w, rows, order, slot_token, xe, h, ye, hd, dense, partial, total;
+    size_t logits, wg_frags, hist, expert_idx, slot_idx, gate_w, rows, order, slot_token, xe, h, ye, hd, dense, partial, total;
 };
 
 WsLayout ws_layout(const moe_shape_t* s) {
@@ -143,6 +143,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
     L.logits = take(T * E * 4);
+    L.wg_frags = take(s->dtype == MOE_BF16 ? gate_bf16_ws_bytes(s->d_model, s->E) : 0);
     L.hist = take(route_scratch_ints(s->T, s->E, s->top_k) * 4);
     L.expert_idx = take(T * k * 4);
     L.slot_idx = take(T * k * 4);
@@ -165,6 +166,14 @@ template <typename T> inline T* at(void* ws, size_t off) { return reinterpret_ca
 int check_ws(const moe_shape_t* s, const void* ws, size_t ws_bytes) {
     if (!ws || !aligned16(ws) || ws_bytes < ws_layout(s).total) return MOE_ERR_WORKSPACE;
     return MOE_OK;
+}
+
+// gate logits: bf16 tokens go to the bf16 matrix cores when the shape allows, everything else to the fp32 ones
+int run_gate_logits(const moe_shape_t* s, const void* x, const float* Wg, const float* bg, float* logits, void* ws,
+                    const WsLayout& L, hipStream_t st) {
+    if (s->dtype == MOE_BF16 && gate_bf16_supported(s->d_model, s->E) && !tune(KN_F32GATE))
+        return launch_gate_logits_bf16(x, Wg, bg, logits, s->T, s->d_model, s->E, at<void>(ws, L.wg_frags), st);
+    return launch_gate_logits(x, s->dtype, Wg, bg, logits, s->T, s->d_model, s->E, st);
 }
 
 // the two GEMMs of an FFN on the plain fp32-ALU kernel (fp32 layers)
@@ -298,7 +307,7 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* lg = logits ? logits : at<float>(ws, L.logits);
     if (x) {
-        rc = launch_gate_logits(x, shape->dtype, Wg, bg, lg, shape->T, shape->d_model, shape->E, st);
+        rc = run_gate_logits(shape, x, Wg, bg, lg, ws, L, st);
         if (rc != MOE_OK) return rc;
     }
     return launch_route(lg, shape->T, shape->E, shape->top_k, shape->capacity, expert_idx, slot_idx, gate_w,
@@ -383,7 +392,7 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
 
     prof_begin(st);
     prof_pre(ST_LOGITS, st);
-    rc = launch_gate_logits(x, dt, Wg, bg, logits, T, d, E, st);
+    rc = run_gate_logits(shape, x, Wg, bg, logits, ws, L, st);
     prof_mark(ST_LOGITS, st);
     if (rc != MOE_OK) return rc;
     int32_t* order = at<int32_t>(ws, L.order);

@@ -60,6 +60,13 @@ template <> struct Elem<uint16_t> {
 int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* bg, float* logits,
                        int T, int d, int E, hipStream_t s);
 
+// the same for bf16 tokens on the bf16 matrix cores (fp32 weights split into three bf16 pieces, exact);
+// frag_ws: gate_bf16_ws_bytes(d, E) bytes of scratch for the split weights, rewritten by every call
+bool gate_bf16_supported(int d, int E);
+size_t gate_bf16_ws_bytes(int d, int E);
+int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
+                            void* frag_ws, hipStream_t s);
+
 // number of int32 the routing kernels need as scratch
 size_t route_scratch_ints(int T, int E, int k);
 
