@@ -82,10 +82,11 @@ struct FfnPlan {
 };
 
 // developer tuning knobs (environment, read once), 0 = not set
-enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_COUNT };
+enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_UNFUSEDGATE, KN_COUNT };
 int tune(Knob k) {
     static const char* const names[KN_COUNT] = {"MOE_TUNE_NBUF", "MOE_TUNE_MT", "MOE_TUNE_NW1", "MOE_TUNE_NW2",
-                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE", "MOE_TUNE_F32GATE"};
+                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE", "MOE_TUNE_F32GATE",
+                                                "MOE_TUNE_UNFUSEDGATE"};
     static int values[KN_COUNT];
     static bool read = false;
     if (!read) {
@@ -174,6 +175,38 @@ int run_gate_logits(const moe_shape_t* s, const void* x, const float* Wg, const 
     if (s->dtype == MOE_BF16 && gate_bf16_supported(s->d_model, s->E) && !tune(KN_F32GATE))
         return launch_gate_logits_bf16(x, Wg, bg, logits, s->T, s->d_model, s->E, at<void>(ws, L.wg_frags), st);
     return launch_gate_logits(x, s->dtype, Wg, bg, logits, s->T, s->d_model, s->E, st);
+}
+
+// the whole gate from tokens: logits (ST_LOGITS; with bf16 tokens and enough of them this kernel also does the
+// top-k and the tile-local ranking) and the rest of the routing (ST_ROUTE)
+int run_gate(const moe_shape_t* s, const void* x, const float* Wg, const float* bg, float* logits, int32_t* expert_idx,
+             int32_t* slot_idx, float* gate_w, int32_t* rows, int32_t* slot_token, int32_t* order, void* ws,
+             const WsLayout& L, bool profile, hipStream_t st) {
+    int32_t* scratch = at<int32_t>(ws, L.hist);
+    int rc;
+    if (s->dtype == MOE_BF16 && gate_bf16_fused_supported(s->T, s->d_model, s->E) && !tune(KN_F32GATE) && !tune(KN_UNFUSEDGATE)) {
+        int tb = 0;
+        const int32_t *hist = nullptr, *coarse = nullptr;
+        if (profile) prof_pre(ST_LOGITS, st);
+        rc = launch_gate_bf16_fused(x, Wg, bg, logits, s->T, s->d_model, s->E, s->top_k, expert_idx, slot_idx, gate_w,
+                                    at<void>(ws, L.wg_frags), scratch, &tb, &hist, &coarse, st);
+        if (profile) prof_mark(ST_LOGITS, st);
+        if (rc != MOE_OK) return rc;
+        if (profile) prof_pre(ST_ROUTE, st);
+        rc = launch_route_finalize(s->T, s->E, s->top_k, s->capacity, tb, expert_idx, slot_idx, rows, slot_token, order,
+                                   hist, coarse, st);
+        if (profile) prof_mark(ST_ROUTE, st);
+        return rc;
+    }
+    if (profile) prof_pre(ST_LOGITS, st);
+    rc = run_gate_logits(s, x, Wg, bg, logits, ws, L, st);
+    if (profile) prof_mark(ST_LOGITS, st);
+    if (rc != MOE_OK) return rc;
+    if (profile) prof_pre(ST_ROUTE, st);
+    rc = launch_route(logits, s->T, s->E, s->top_k, s->capacity, expert_idx, slot_idx, gate_w, rows, slot_token, order,
+                      scratch, st);
+    if (profile) prof_mark(ST_ROUTE, st);
+    return rc;
 }
 
 // the two GEMMs of an FFN on the plain fp32-ALU kernel (fp32 layers)
@@ -306,10 +339,8 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
     const WsLayout L = ws_layout(shape);
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* lg = logits ? logits : at<float>(ws, L.logits);
-    if (x) {
-        rc = run_gate_logits(shape, x, Wg, bg, lg, ws, L, st);
-        if (rc != MOE_OK) return rc;
-    }
+    if (x)
+        return run_gate(shape, x, Wg, bg, lg, expert_idx, slot_idx, gate_w, expert_rows, slot_token, nullptr, ws, L, false, st);
     return launch_route(lg, shape->T, shape->E, shape->top_k, shape->capacity, expert_idx, slot_idx, gate_w,
                         expert_rows, slot_token, nullptr, at<int32_t>(ws, L.hist), st);
 }
@@ -391,15 +422,8 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     int32_t* slot_token = slot_token_out ? slot_token_out : at<int32_t>(ws, L.slot_token);
 
     prof_begin(st);
-    prof_pre(ST_LOGITS, st);
-    rc = run_gate_logits(shape, x, Wg, bg, logits, ws, L, st);
-    prof_mark(ST_LOGITS, st);
-    if (rc != MOE_OK) return rc;
     int32_t* order = at<int32_t>(ws, L.order);
-    prof_pre(ST_ROUTE, st);
-    rc = launch_route(logits, T, E, k, C, expert_idx, slot_idx, gate_w, rows, slot_token, order,
-                      at<int32_t>(ws, L.hist), st);
-    prof_mark(ST_ROUTE, st);
+    rc = run_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, rows, slot_token, order, ws, L, true, st);
     if (rc != MOE_OK) return rc;
     const FfnPlan plan = plan_ffn(shape);
     if (!plan.mfma) {

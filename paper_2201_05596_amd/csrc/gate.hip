@@ -10,7 +10,7 @@
 // is deterministic (no atomics) and needs two small launches.
 #include <cstdlib>
 
-#include "moe_internal.h"
+#include "gate_common.h"
 
 namespace moe {
 
@@ -240,108 +240,6 @@ int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* b
 //            the block is parked in slot_idx until kernel 2 adds the block's base.
 // scratch layout: hist[block][choice][E]
 // ------------------------------------------------------------------------------------------
-struct Best {
-    float v;
-    int i;
-};
-__device__ __forceinline__ Best better(Best a, Best b) {
-    return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
-}
-// All-reduce inside aligned groups of 16 lanes (one DPP "row") with data-parallel-primitive moves:
-// swap inside pairs, swap pairs inside quads, mirror the two quads of each half row, mirror the two
-// half rows.  After step i every aligned group of 2^i lanes holds one common value, which is what
-// makes the mirrors (which reverse lane order) as good as butterflies.  No LDS traffic, unlike
-// __shfl_xor.
-constexpr int kDppSwap1 = 0xB1;        // quad_perm [1,0,3,2]
-constexpr int kDppSwap2 = 0x4E;        // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;  // row_half_mirror
-constexpr int kDppMirror = 0x140;      // row_mirror
-template <int CTRL> __device__ __forceinline__ int dpp_i(int v) {
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
-}
-template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
-    return __int_as_float(dpp_i<CTRL>(__float_as_int(v)));
-}
-template <int CTRL> __device__ __forceinline__ Best best_step(Best a) {
-    Best o;
-    o.v = dpp_f<CTRL>(a.v);
-    o.i = dpp_i<CTRL>(a.i);
-    return better(a, o);
-}
-__device__ __forceinline__ Best group_best(Best a) {
-    a = best_step<kDppSwap1>(a);
-    a = best_step<kDppSwap2>(a);
-    a = best_step<kDppHalfMirror>(a);
-    a = best_step<kDppMirror>(a);
-    return a;
-}
-// Sum in a fixed tree order; every lane ends with the same bits (each step adds the same two
-// partial sums on both sides, and fp add commutes).
-__device__ __forceinline__ float group_sum(float a) {
-    a += dpp_f<kDppSwap1>(a);
-    a += dpp_f<kDppSwap2>(a);
-    a += dpp_f<kDppHalfMirror>(a);
-    a += dpp_f<kDppMirror>(a);
-    return a;
-}
-
-// exp on the hardware exp2 unit; the argument is <= 0 here and the dominant terms have a small
-// argument, which keeps the softmax weights within ~1e-7 of the exact value
-__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
-
-template <int K>
-__device__ __forceinline__ void gate_weights(float s, Best g1, Best g2, float& w1, float& w2) {
-    if (K == 1) {
-        w1 = 1.0f / s;                          // softmax probability of the arg-max
-        w2 = 0.f;
-    } else {
-        const float r = fast_exp(g2.v - g1.v);  // p2/p1; renormalised pair = (1, r)/(1 + r)
-        w1 = 1.0f / (1.0f + r);
-        w2 = r / (1.0f + r);
-    }
-}
-
-// Top-K experts and gate weights of one token, computed by a group of 16 lanes; lane `sub` looks
-// at experts sub, sub+16, ...  Every lane of the group returns the same result.
-// Register version: the lane's NV logits are already loaded (padding = -inf).
-template <int K, int NV>
-__device__ __forceinline__ void token_gate_regs(const float (&v)[NV], int sub, Best& g1, Best& g2, float& w1,
-                                                float& w2) {
-    const Best none{-INFINITY, 0x7fffffff};
-    Best b1 = none, b2 = none;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int e = sub + 16 * i;
-        if (v[i] > b1.v) { b2 = b1; b1.v = v[i]; b1.i = e; }
-        else if (v[i] > b2.v) { b2.v = v[i]; b2.i = e; }
-    }
-    g1 = group_best(b1);
-    g2 = none;
-    if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) s += fast_exp(v[i] - g1.v);       // exp(-inf) = 0 for the padding
-    gate_weights<K>(group_sum(s), g1, g2, w1, w2);
-}
-// Any E: two passes over the row in memory.
-template <int K>
-__device__ __forceinline__ void token_gate_mem(const float* __restrict__ row, int E, int sub, Best& g1, Best& g2,
-                                               float& w1, float& w2) {
-    const Best none{-INFINITY, 0x7fffffff};
-    Best b1 = none, b2 = none;
-    for (int e = sub; e < E; e += 16) {
-        const float v = row[e];
-        if (v > b1.v) { b2 = b1; b1.v = v; b1.i = e; }
-        else if (v > b2.v) { b2.v = v; b2.i = e; }
-    }
-    g1 = group_best(b1);
-    g2 = none;
-    if (K == 2) g2 = group_best(b1.i == g1.i ? b2 : b1);
-    float s = 0.f;
-    for (int e = sub; e < E; e += 16) s += fast_exp(row[e] - g1.v);
-    gate_weights<K>(group_sum(s), g1, g2, w1, w2);
-}
-
 template <int K, int NV>
 __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* __restrict__ logits, int T, int E,
                                                                    int32_t* __restrict__ expert_idx,
@@ -412,21 +310,10 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 
     // phase B
     int my_e[K], my_rank[K];
-    const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-        const int e = e_sh[j * kRouteTokens + tid];
-        my_e[j] = e;
-        my_rank[j] = 0;
-        unsigned long long todo = __ballot(e >= 0);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int le = __shfl(e, leader, kWave);
-            const unsigned long long m = __ballot(e == le);
-            if (e == le) my_rank[j] = __popcll(m & lt_mask);
-            if (lane == leader) whist[(w * K + j) * E + le] = __popcll(m);
-            todo &= ~m;
-        }
+        my_e[j] = e_sh[j * kRouteTokens + tid];
+        my_rank[j] = wave_rank_by_expert(my_e[j], lane, whist + (w * K + j) * E);
     }
     __syncthreads();
 
@@ -512,31 +399,35 @@ int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+// hist holds one histogram [K][E] per block of TB tokens (TB divides 256), coarse one per 256 tokens
+// (the sum of its 256/TB fine ones; the same array when TB is 256).  A work-group finalises 256 tokens.
 template <int K>
-__global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int E, int C, int nblocks,
+__global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int E, int C, int nblocks, int TB,
                                                                       const int32_t* __restrict__ expert_idx,
                                                                       int32_t* __restrict__ slot_idx,
                                                                       int32_t* __restrict__ expert_rows,
                                                                       int32_t* __restrict__ slot_token,
                                                                       int32_t* __restrict__ expert_order,
-                                                                      const int32_t* __restrict__ hist) {
+                                                                      const int32_t* __restrict__ hist,
+                                                                      const int32_t* __restrict__ coarse) {
     extern __shared__ int32_t smem[];
-    int32_t* base = smem;             // [K][E]
-    int32_t* rows_sh = smem + K * E;  // [E]
+    const int ncol = K * E;                                // column = (choice j, expert e)
+    const int q = kRouteTokens / TB;                       // fine blocks per work-group
+    int32_t* base = smem;                                  // [q][K][E] rows before the fine block's tokens
+    int32_t* rows_sh = base + q * ncol;                    // [E]
+    int32_t* part = rows_sh + E;                           // [2][R][ncol]: before-me sums, all-blocks sums
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
 
-    // column = (choice j, expert e); the blocks' histograms are summed with all 256 threads: R row
-    // groups each take every R-th block, partial sums meet in LDS
-    const int ncol = K * E;
-    int32_t* part = rows_sh + E;                           // [2][R][ncol]: before-me sums, all-blocks sums
+    // the coarse histograms are summed with all 256 threads: R row groups each take every R-th block,
+    // partial sums meet in LDS
     const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
     for (int idx = tid; idx < R * ncol; idx += kRouteTokens) {
         const int col = idx % ncol, rg = idx / ncol;
         int pre = 0, tot = 0;
 #pragma unroll 8
         for (int bb = rg; bb < nblocks; bb += R) {
-            const int v = hist[(size_t)bb * ncol + col];
+            const int v = coarse[(size_t)bb * ncol + col];
             tot += v;
             pre += bb < b ? v : 0;
         }
@@ -554,11 +445,20 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
                 tot[j] += part[(R + rg) * ncol + j * E + e];
             }
         }
-        base[e] = pre[0];
+        // first choices: rows before = first choices of earlier tokens; second choices rank behind ALL first ones
+        int run[K];
+        run[0] = pre[0];
         int total = tot[0];
         if (K == 2) {
-            base[E + e] = tot[0] + pre[1];
+            run[1] = tot[0] + pre[1];
             total += tot[1];
+        }
+        for (int f = 0; f < q; ++f) {
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                base[(f * K + j) * E + e] = run[j];
+                if (f + 1 < q && (b * q + f) * TB < T) run[j] += hist[((size_t)(b * q + f) * K + j) * E + e];
+            }
         }
         rows_sh[e] = min(total, C);
     }
@@ -566,10 +466,11 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
 
     const int t = b * kRouteTokens + tid;
     if (t < T) {
+        const int f = tid / TB;
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             const int e = expert_idx[(size_t)t * K + j];
-            const int loc = base[j * E + e] + slot_idx[(size_t)t * K + j];
+            const int loc = base[(f * K + j) * E + e] + slot_idx[(size_t)t * K + j];
             if (loc < C) {
                 slot_idx[(size_t)t * K + j] = loc;
                 slot_token[(size_t)e * C + loc] = t;
@@ -593,9 +494,32 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
     }
 }
 
+size_t route_finalize_lds_bytes(int E, int k, int TB) {
+    const int ncol = k * E;
+    const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
+    size_t ints = (size_t)(kRouteTokens / TB) * ncol + E + 2 * (size_t)R * ncol;
+    if (ints < (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 1) ints = (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 1;
+    return ints * sizeof(int32_t);
+}
+
+int launch_route_finalize(int T, int E, int k, int C, int TB, const int32_t* expert_idx, int32_t* slot_idx,
+                          int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order, const int32_t* hist,
+                          const int32_t* coarse, hipStream_t s) {
+    const int nb = (T + kRouteTokens - 1) / kRouteTokens;
+    const size_t sm = route_finalize_lds_bytes(E, k, TB);
+    if (k == 1)
+        hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(nb), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
+                           slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
+    else
+        hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(nb), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
+                           slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// fine histograms for blocks of 32 tokens at the finest, plus the coarse ones
 size_t route_scratch_ints(int T, int E, int k) {
-    const size_t nb = ((size_t)T + kRouteTokens - 1) / kRouteTokens;
-    return nb * (size_t)k * (size_t)E;
+    const size_t fine = ((size_t)T + 31) / 32, coarse = ((size_t)T + kRouteTokens - 1) / kRouteTokens;
+    return (fine + coarse) * (size_t)k * (size_t)E;
 }
 
 int launch_route(const float* logits, int T, int E, int k, int C, int32_t* expert_idx, int32_t* slot_idx,
@@ -604,9 +528,6 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const int NW = kRouteTokens / kWave;
     const size_t sm1 = sizeof(int32_t) * ((size_t)k * kRouteTokens + (size_t)NW * k * E);
-    const int ncol = k * E;
-    const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
-    const size_t sm2 = sizeof(int32_t) * ((size_t)k * E + E + 2 * (size_t)R * ncol);
 #define MOE_ROUTE_LOCAL(K, NV)                                                                                   \
     hipLaunchKernelGGL((route_local_kernel<K, NV>), dim3(nb), dim3(kRouteTokens), sm1, s, logits, T, E, expert_idx, \
                        slot_idx, gate_w, scratch)
@@ -616,19 +537,18 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
         else if (E <= 64) MOE_ROUTE_LOCAL(1, 4);
         else if (E <= 128) MOE_ROUTE_LOCAL(1, 8);
         else MOE_ROUTE_LOCAL(1, 0);
-        hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
-                           expert_idx, slot_idx, expert_rows, slot_token, expert_order, scratch);
     } else {
         if (E <= 16) MOE_ROUTE_LOCAL(2, 1);
         else if (E <= 32) MOE_ROUTE_LOCAL(2, 2);
         else if (E <= 64) MOE_ROUTE_LOCAL(2, 4);
         else if (E <= 128) MOE_ROUTE_LOCAL(2, 8);
         else MOE_ROUTE_LOCAL(2, 0);
-        hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(nb), dim3(kRouteTokens), sm2, s, T, E, C, nb,
-                           expert_idx, slot_idx, expert_rows, slot_token, expert_order, scratch);
     }
 #undef MOE_ROUTE_LOCAL
-    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    // the block histograms are per 256 tokens: fine and coarse coincide
+    return launch_route_finalize(T, E, k, C, kRouteTokens, expert_idx, slot_idx, expert_rows, slot_token, expert_order,
+                                 scratch, scratch, s);
 }
 
 }  // namespace moe

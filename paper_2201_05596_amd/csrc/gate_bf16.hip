@@ -1,6 +1,7 @@
-// Gate logits for bf16 tokens on the bf16 matrix cores, exact to fp32 level (paper Sec. 5.4: the gate
-// is the first of the three MoE components; its matrix product is small but sits on the critical path
-// before every other kernel of the layer).
+// Gate for bf16 tokens on the bf16 matrix cores, exact to fp32 level (paper Sec. 5.4: the gating
+// function -- logits, top-k, the count that places a token inside its expert -- fused into as few
+// kernels as the data dependences allow; it is small but sits on the critical path before every other
+// kernel of the layer).
 //
 //   logits[t,e] = bg[e] + sum_i x[t,i] Wg[i,e],   x bf16, Wg and bg fp32, fp32 accumulation.
 //
@@ -9,19 +10,25 @@
 // value times a bf16 piece is exact in fp32, so three v_mfma_f32_16x16x32_bf16 per tile give the same
 // sum of exact products as an fp32 multiply-add chain, at a fraction of the fp32 matrix-core time.
 //
-// Two kernels:
-//   * wg_split_kernel writes the three pieces as ready-made MFMA B fragments (1 KB each: lane l holds
-//     k = 8*(l/16)..+7 of expert column l%16), ordered [k-block][expert tile][piece];
-//   * gate_logits_bf16_kernel: a work-group owns a tile of 16*MA tokens x 16*NE experts; its four waves
+// Kernels:
+//   * gate_prepare_kernel writes the three pieces as ready-made MFMA B fragments (1 KB each: lane l
+//     holds k = 8*(l/16)..+7 of expert column l%16), ordered [k-block][expert tile][piece], and clears
+//     the coarse routing histograms;
+//   * gate_bf16_kernel: a work-group owns a tile of 16*MA tokens x 16*NE experts; its four waves
 //     split the k-blocks (wave w takes blocks w, w+4, ...) and each computes the whole tile for its
-//     blocks, so no operand byte is fetched twice by a work-group; the four partial tiles are summed
-//     through LDS in fixed order.  Every operand fragment is one 16-byte load per lane from global
-//     memory straight into registers, several k-blocks ahead; no LDS traffic and no barrier in the
-//     loop.  The kernel is bound by the rate at which a CU can pull operands out of L2 (about
-//     50-70 GB/s per CU measured, direct-to-LDS loads no faster), so the tile is chosen to minimise
-//     bytes per CU while still giving every CU a work-group.
+//     blocks, so no operand byte is fetched twice by a work-group.  Every operand fragment is one
+//     16-byte load per lane from global memory straight into registers, several k-blocks ahead; no LDS
+//     traffic and no barrier in the loop.  The four partial tiles are summed through LDS in a fixed
+//     order, the finished tile is laid out [token][expert] in LDS and written with 16-byte stores.
+//     When the tile spans all experts (K = 1 or 2) the kernel goes on to the first half of the
+//     routing on the tile it holds: top-k and gate weights per token (16 lanes per token), the rank of
+//     each token among the tile's tokens with the same expert (ballots), the tile's histogram, and its
+//     sum into the histogram of the enclosing block of 256 tokens (integer atomics: the result does not
+//     depend on their order).  route_finalize_kernel turns ranks into rows.
+//     With few tokens the experts are split over work-groups instead (K = 0: logits only) so that
+//     more CUs take part, and the routing runs as a kernel of its own.
 // Requires d_model to be a multiple of 32 and at most 128 experts; other shapes use the fp32 kernel.
-#include "moe_internal.h"
+#include "gate_common.h"
 
 namespace moe {
 
@@ -33,10 +40,11 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kKB = 32;                  // k per MFMA
 constexpr int kFragElems = 512;          // bf16 elements of one fragment (64 lanes x 8)
-// KB k-blocks x ET expert tiles x 3 pieces; one thread per (k-block, expert tile, lane)
-__global__ __launch_bounds__(256) void wg_split_kernel(const float* __restrict__ Wg, uint16_t* __restrict__ frags, int d,
-                                                       int E, int KB, int ET) {
+// KB k-blocks x ET expert tiles x 3 pieces; one thread per (k-block, expert tile, lane).  Also clears `zero`.
+__global__ __launch_bounds__(256) void gate_prepare_kernel(const float* __restrict__ Wg, uint16_t* __restrict__ frags, int d,
+                                                           int E, int KB, int ET, int32_t* __restrict__ zero, int nzero) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    for (long long i = idx; i < nzero; i += (long long)gridDim.x * 256) zero[i] = 0;
     if (idx >= (long long)KB * ET * 64) return;
     const int lane = (int)(idx & 63);
     const long long fe = idx >> 6;
@@ -65,25 +73,48 @@ __global__ __launch_bounds__(256) void wg_split_kernel(const float* __restrict__
 
 template <int MA, int NE> struct GateCfg {
     static constexpr int PER = MA + 3 * NE;                                  // 16-byte loads per lane and k-block
-    static constexpr int D = 48 / PER < 3 ? 3 : (48 / PER > 6 ? 6 : 48 / PER);   // k-blocks held in registers
+    static constexpr int D = PER > 24 ? 2 : (48 / PER < 3 ? 3 : (48 / PER > 6 ? 6 : 48 / PER));   // k-blocks held in registers
 };
 
 // tile: MA token tiles (16 tokens each) x NE expert tiles; blockIdx.x = token tile, blockIdx.y = expert group;
-// ET = expert tiles in all (fragment stride)
-template <int MA, int NE>
-__global__ __launch_bounds__(256) void gate_logits_bf16_kernel(const uint16_t* __restrict__ x,
-                                                               const uint16_t* __restrict__ frags,
-                                                               const float* __restrict__ bg, float* __restrict__ logits,
-                                                               int T, int d, int E, int ET) {
-    constexpr int D = GateCfg<MA, NE>::D, PER = GateCfg<MA, NE>::PER, WE = 1, WK = 4;
-    __shared__ f32x4_t red[(WK - 1) * WE * MA * NE * 64];
+// ET = expert tiles in all (fragment stride).  K = 0: logits only.  K = 1, 2 (needs NE == ET): also top-K, gate
+// weights, tile-local ranks (parked in slot_idx) and histograms.
+template <int MA, int NE, int K> struct GateLds {
+    static constexpr int TM = 16 * MA, TN = 16 * NE;
+    static constexpr int STRIDE = TN + 4;                         // floats per tile row: 4 rows apart fall 16 banks apart
+    static constexpr int RED = 2 * MA * NE * 64 * 16;             // two partial tiles, bytes
+    static constexpr int TILE = TM * STRIDE * 4;
+    static constexpr int MAIN = RED > TILE ? RED : TILE;          // the finished tile reuses the partial tiles' space
+    static constexpr int ROUTE = K > 0 ? (K * TM + K * TN) * 4 : 0;   // chosen experts, histogram
+    static constexpr int BYTES = MAIN + ROUTE;
+};
+
+template <int MA, int NE, int K>
+__global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ frags,
+                                                        const float* __restrict__ bg, float* __restrict__ logits, int T, int d,
+                                                        int E, int ET, int32_t* __restrict__ expert_idx,
+                                                        int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
+                                                        int32_t* __restrict__ hist, int32_t* __restrict__ coarse) {
+    typedef GateLds<MA, NE, K> L;
+    constexpr int D = GateCfg<MA, NE>::D, PER = GateCfg<MA, NE>::PER, WK = 4, TM = L::TM, TN = L::TN, STRIDE = L::STRIDE;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    f32x4_t* red = reinterpret_cast<f32x4_t*>(lds);               // [2][MA][NE][64]
+    float* tile = reinterpret_cast<float*>(lds);                  // [TM][STRIDE], after the reduction
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int we = 0, wk = w;
+    const int wk = w;
     const int et0 = blockIdx.y * NE;                              // first expert tile of this work-group
-    const int t0 = blockIdx.x * (16 * MA);
+    const int t0 = blockIdx.x * TM;
     const int KB = d / kKB;
     const int nkb = KB > wk ? (KB - wk + WK - 1) / WK : 0;        // k-blocks wk, wk + WK, ... of this wave
+
+    // bias of this lane's expert columns, fetched before anything else is in flight
+    float bias[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+        const int col = (et0 + e) * 16 + (lane & 15);
+        bias[e] = (bg && col < E) ? bg[col] : 0.f;
+    }
 
     f32x4_t acc[MA][NE];
 #pragma unroll
@@ -159,46 +190,134 @@ __global__ __launch_bounds__(256) void gate_logits_bf16_kernel(const uint16_t* _
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the loads fetched ahead past the end
     }
 
-    // ---- sum over the k-splits (fixed order), then bias and store ------------------------------------
-    if (WK > 1) {
-        if (wk > 0) {
+    // ---- sum of the four partial tiles, always as (w0 + w2) + (w1 + w3) ------------------------------
+    if (w >= 2) {
 #pragma unroll
-            for (int m = 0; m < MA; ++m)
+        for (int m = 0; m < MA; ++m)
 #pragma unroll
-                for (int e = 0; e < NE; ++e) red[((((wk - 1) * WE + we) * MA + m) * NE + e) * 64 + lane] = acc[m][e];
-        }
-        __syncthreads();
-        if (wk == 0) {
+            for (int e = 0; e < NE; ++e) red[(((w - 2) * MA + m) * NE + e) * 64 + lane] = acc[m][e];
+    }
+    __syncthreads();
+    if (w < 2) {
 #pragma unroll
-            for (int k = 1; k < WK; ++k)
+        for (int m = 0; m < MA; ++m)
 #pragma unroll
-                for (int m = 0; m < MA; ++m)
+            for (int e = 0; e < NE; ++e) acc[m][e] += red[((w * MA + m) * NE + e) * 64 + lane];
+    }
+    __syncthreads();
+    if (w == 1) {
 #pragma unroll
-                    for (int e = 0; e < NE; ++e) acc[m][e] += red[((((k - 1) * WE + we) * MA + m) * NE + e) * 64 + lane];
+        for (int m = 0; m < MA; ++m)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) red[(m * NE + e) * 64 + lane] = acc[m][e];
+    }
+    __syncthreads();
+    if (w == 0) {
+        // finished logits (bias added) go to LDS as [token][expert]; D fragment: column lane%16, rows 4*(lane/16)+r
+#pragma unroll
+        for (int m = 0; m < MA; ++m)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[m][e] += red[(m * NE + e) * 64 + lane];
+        asm volatile("" ::: "memory");                                // keep the reads above ahead of the writes below
+        // the partial tile just read and the finished tile share LDS: only this wave touches either here,
+        // and its LDS operations execute in order
+#pragma unroll
+        for (int m = 0; m < MA; ++m)
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    tile[(16 * m + 4 * (lane >> 4) + r) * STRIDE + 16 * e + (lane & 15)] = acc[m][e][r] + bias[e];
+    }
+    __syncthreads();
+
+    // ---- logits out: 16 bytes per thread, rows contiguous ------------------------------------------------
+    {
+        constexpr int V = TN / 4;                                 // float4 per tile row
+        const int col0 = et0 * 16;
+        for (int i = tid; i < TM * V; i += 256) {
+            const int tl = i / V, c4 = (i % V) * 4;
+            const int t = t0 + tl, col = col0 + c4;
+            if (t >= T || col >= E) continue;
+            const float4 v = *reinterpret_cast<const float4*>(tile + tl * STRIDE + c4);
+            float* o = logits + (size_t)t * E + col;
+            if ((E & 3) == 0) *reinterpret_cast<float4*>(o) = v;              // col + 3 < E and 16-byte aligned
+            else {
+                o[0] = v.x;
+                if (col + 1 < E) o[1] = v.y;
+                if (col + 2 < E) o[2] = v.z;
+                if (col + 3 < E) o[3] = v.w;
+            }
         }
     }
-    if (wk == 0) {
+
+    if (K > 0) {
+        constexpr int KK = K > 0 ? K : 1;
+        int32_t* e_sh = reinterpret_cast<int32_t*>(lds + L::MAIN);    // [K][TM] chosen expert per token of the tile
+        int32_t* h_sh = e_sh + KK * TM;                               // [K][TN] histogram of the tile
+        for (int i = tid; i < KK * TN; i += 256) h_sh[i] = 0;
+        // 16 lanes per token, 16 tokens at a time
+        const int grp = tid >> 4, sub = tid & 15;
 #pragma unroll
-        for (int e = 0; e < NE; ++e) {
-            const int col = (et0 + e) * 16 + (lane & 15);     // D: column lane%16, rows 4*(lane/16)+r
-            if (col >= E) continue;
-            const float b = bg ? bg[col] : 0.f;
+        for (int it = 0; it < MA; ++it) {
+            const int tl = it * 16 + grp;
+            float v[NE];
 #pragma unroll
-            for (int m = 0; m < MA; ++m)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int t = t0 + 16 * m + 4 * (lane >> 4) + r;
-                    if (t < T) logits[(size_t)t * E + col] = acc[m][e][r] + b;
+            for (int i = 0; i < NE; ++i) v[i] = sub + 16 * i < E ? tile[tl * STRIDE + sub + 16 * i] : -INFINITY;
+            Best g1, g2;
+            float w1, w2;
+            token_gate_regs<KK, NE>(v, sub, g1, g2, w1, w2);
+            if (sub == 0) {
+                const int t = t0 + tl;
+                const bool ok = t < T;
+                e_sh[tl] = ok ? g1.i : -1;
+                if (KK == 2) e_sh[TM + tl] = ok ? g2.i : -1;
+                if (ok) {
+                    expert_idx[(size_t)t * KK] = g1.i;
+                    gate_w[(size_t)t * KK] = w1;
+                    if (KK == 2) {
+                        expert_idx[(size_t)t * KK + 1] = g2.i;
+                        gate_w[(size_t)t * KK + 1] = w2;
+                    }
                 }
+            }
+        }
+        __syncthreads();
+        // one lane per token (the tile has at most 64): rank among the tile's tokens with the same expert
+        if (w == 0) {
+#pragma unroll
+            for (int j = 0; j < KK; ++j) {
+                const int e = lane < TM ? e_sh[j * TM + lane] : -1;
+                const int rank = wave_rank_by_expert(e, lane, h_sh + j * TN);
+                if (e >= 0) slot_idx[(size_t)(t0 + lane) * KK + j] = rank;
+            }
+        }
+        __syncthreads();
+        // histogram [K][E] of this tile, and its share of the enclosing 256-token block's
+        constexpr int FINE_PER_COARSE = kRouteTokens / TM;
+        for (int i = tid; i < KK * E; i += 256) {
+            const int j = i / E, e = i % E;
+            const int c = h_sh[j * TN + e];
+            hist[(size_t)blockIdx.x * KK * E + i] = c;
+            if (c) atomicAdd(&coarse[(size_t)(blockIdx.x / FINE_PER_COARSE) * KK * E + i], c);
         }
     }
 }
 
-template <int MA, int NE>
+template <int MA, int NE, int K>
 int launch_cfg(const uint16_t* x, const uint16_t* frags, const float* bg, float* logits, int T, int d, int E, int ET,
-               hipStream_t s) {
+               int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* hist, int32_t* coarse, hipStream_t s) {
+    constexpr int smem = GateLds<MA, NE, K>::BYTES;
+    static bool attr_set = false;             // one flag per instantiation
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bf16_kernel<MA, NE, K>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_set = true;
+    }
     const dim3 grid((T + 16 * MA - 1) / (16 * MA), ET / NE);
-    hipLaunchKernelGGL((gate_logits_bf16_kernel<MA, NE>), grid, dim3(256), 0, s, x, frags, bg, logits, T, d, E, ET);
+    hipLaunchKernelGGL((gate_bf16_kernel<MA, NE, K>), grid, dim3(256), smem, s, x, frags, bg, logits, T, d, E, ET, expert_idx,
+                       slot_idx, gate_w, hist, coarse);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -217,14 +336,21 @@ size_t gate_bf16_ws_bytes(int d, int E) {
     return (size_t)(d / kKB) * padded_expert_tiles(E) * 3 * kFragElems * sizeof(uint16_t);
 }
 
+static int launch_prepare(const float* Wg, uint16_t* frags, int d, int E, int KB, int ET, int32_t* zero, int nzero,
+                          hipStream_t s) {
+    const long long threads = (long long)KB * ET * 64;
+    hipLaunchKernelGGL(gate_prepare_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, Wg, frags, d, E, KB, ET,
+                       zero, nzero);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
                             void* frag_ws, hipStream_t s) {
     if (!gate_bf16_supported(d, E) || !frag_ws) return MOE_ERR_INVALID_ARG;
     const int KB = d / kKB, ET = padded_expert_tiles(E);
     uint16_t* frags = static_cast<uint16_t*>(frag_ws);
-    const long long threads = (long long)KB * ET * 64;
-    hipLaunchKernelGGL(wg_split_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, Wg, frags, d, E, KB, ET);
-    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    const int rc = launch_prepare(Wg, frags, d, E, KB, ET, nullptr, 0, s);
+    if (rc != MOE_OK) return rc;
     const uint16_t* xb = static_cast<const uint16_t*>(x);
     // Largest tile (fewest operand bytes per output) that still gives every CU a work-group; when even
     // the smallest tile cannot (few tokens), the smallest one: most work-groups, least time per CU.
@@ -234,11 +360,46 @@ int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, flo
         for (int ne = ET < 4 ? ET : 4; ne >= 1 && !found; ne /= 2)
             if ((long long)((T + 16 * ma - 1) / (16 * ma)) * (ET / ne) >= 256) { MA = ma; NE = ne; found = true; }
 #define MOE_GATE_CASE(ma, ne) \
-    if (MA == ma && NE == ne) return launch_cfg<ma, ne>(xb, frags, bg, logits, T, d, E, ET, s)
+    if (MA == ma && NE == ne)   \
+    return launch_cfg<ma, ne, 0>(xb, frags, bg, logits, T, d, E, ET, nullptr, nullptr, nullptr, nullptr, nullptr, s)
     MOE_GATE_CASE(4, 4); MOE_GATE_CASE(4, 2); MOE_GATE_CASE(4, 1);
     MOE_GATE_CASE(2, 4); MOE_GATE_CASE(2, 2); MOE_GATE_CASE(2, 1);
 #undef MOE_GATE_CASE
     return MOE_ERR_INVALID_ARG;
+}
+
+// With fewer tokens the fused kernel would leave most CUs idle; logits over expert groups plus a separate
+// routing kernel is faster then.
+bool gate_bf16_fused_supported(int T, int d, int E) { return gate_bf16_supported(d, E) && T >= 2048; }
+
+int launch_gate_bf16_fused(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E, int k,
+                           int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws, int32_t* scratch,
+                           int* tokens_per_hist, const int32_t** hist_out, const int32_t** coarse_out, hipStream_t s) {
+    if (!gate_bf16_fused_supported(T, d, E) || !frag_ws || !scratch || k < 1 || k > 2) return MOE_ERR_INVALID_ARG;
+    const int KB = d / kKB, ET = padded_expert_tiles(E);
+    uint16_t* frags = static_cast<uint16_t*>(frag_ws);
+    // 64-token tiles once they give every CU a work-group, else 32-token ones
+    const int MA = (T + 63) / 64 >= 256 ? 4 : 2;
+    const int TM = 16 * MA;
+    const int nfine = (T + TM - 1) / TM, ncoarse = (T + kRouteTokens - 1) / kRouteTokens;
+    int32_t* hist = scratch;
+    int32_t* coarse = scratch + (size_t)nfine * k * E;            // within route_scratch_ints(T, E, k)
+    int rc = launch_prepare(Wg, frags, d, E, KB, ET, coarse, ncoarse * k * E, s);
+    if (rc != MOE_OK) return rc;
+    const uint16_t* xb = static_cast<const uint16_t*>(x);
+    rc = MOE_ERR_INVALID_ARG;
+#define MOE_GATE_CASE(ma, ne, kk) \
+    if (MA == ma && ET == ne && k == kk) \
+    rc = launch_cfg<ma, ne, kk>(xb, frags, bg, logits, T, d, E, ET, expert_idx, slot_idx, gate_w, hist, coarse, s)
+    MOE_GATE_CASE(4, 8, 1); MOE_GATE_CASE(4, 4, 1); MOE_GATE_CASE(4, 2, 1); MOE_GATE_CASE(4, 1, 1);
+    MOE_GATE_CASE(2, 8, 1); MOE_GATE_CASE(2, 4, 1); MOE_GATE_CASE(2, 2, 1); MOE_GATE_CASE(2, 1, 1);
+    MOE_GATE_CASE(4, 8, 2); MOE_GATE_CASE(4, 4, 2); MOE_GATE_CASE(4, 2, 2); MOE_GATE_CASE(4, 1, 2);
+    MOE_GATE_CASE(2, 8, 2); MOE_GATE_CASE(2, 4, 2); MOE_GATE_CASE(2, 2, 2); MOE_GATE_CASE(2, 1, 2);
+#undef MOE_GATE_CASE
+    *tokens_per_hist = TM;
+    *hist_out = hist;
+    *coarse_out = coarse;
+    return rc;
 }
 
 }  // namespace moe
