@@ -73,7 +73,9 @@ __global__ __launch_bounds__(256) void gate_prepare_kernel(const float* __restri
 
 template <int MA, int NE> struct GateCfg {
     static constexpr int PER = MA + 3 * NE;                                  // 16-byte loads per lane and k-block
-    static constexpr int D = PER > 24 ? 2 : (48 / PER < 3 ? 3 : (48 / PER > 6 ? 6 : 48 / PER));   // k-blocks held in registers
+    // k-blocks held in registers: as many as fit beside the accumulators (4 registers per load and per tile)
+    static constexpr int D_WANT = 48 / PER < 3 ? 3 : (48 / PER > 6 ? 6 : 48 / PER);
+    static constexpr int D = 4 * (MA * NE + D_WANT * PER) <= 400 ? D_WANT : 2;
 };
 
 // tile: MA token tiles (16 tokens each) x NE expert tiles; blockIdx.x = token tile, blockIdx.y = expert group;
@@ -131,30 +133,20 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
         const uint16_t* b_src = frags + (size_t)et0 * 3 * kFragElems + lane * 8;
         const size_t b_kb_stride = (size_t)ET * 3 * kFragElems;
 
-        // Operands of one k-block: A fragments straight from the token rows, B fragments as stored.  The
-        // loads and the waits for them are written by hand: the compiler's own bookkeeping of outstanding
-        // loads gives up at the back edge of a rotating register ring and waits for nearly all of them.
-        // Loads return in order, so "all but the newest (D-1)*PER" means the oldest k-block has arrived;
-        // the wait names that block's registers as operands, which orders every use after it.
+        // Operands of one k-block: A fragments straight from the token rows, B fragments as stored.
+        // Plain loads: the compiler tracks their completion.  (Loads issued from inline asm with
+        // hand-placed waits are NOT an option here: the compiler regards an asm output as valid at once
+        // and, under register pressure, copies it elsewhere before the data has arrived.)
         struct Stage {
             u32x4_t r[PER];                                       // MA token fragments, then 3*NE weight fragments
         };
         auto load = [&](Stage& st, int step) {
             const int kb = wk + min(step, nkb - 1) * WK;          // past the end: harmless re-read, dropped
 #pragma unroll
-            for (int m = 0; m < MA; ++m)
-                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(st.r[m]) : "v"(a_src[m] + kb * kKB) : "memory");
+            for (int m = 0; m < MA; ++m) st.r[m] = *reinterpret_cast<const u32x4_t*>(a_src[m] + kb * kKB);
             const uint16_t* bp = b_src + (size_t)kb * b_kb_stride;
 #pragma unroll
-            for (int i = 0; i < 3 * NE; ++i)
-                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(st.r[MA + i]) : "v"(bp + i * kFragElems) : "memory");
-        };
-        auto arrived = [&](Stage& st) {
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                if (i == 0) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(st.r[i]) : "n"((D - 1) * PER) : "memory");
-                else asm volatile("" : "+v"(st.r[i]));
-            }
+            for (int i = 0; i < 3 * NE; ++i) st.r[MA + i] = *reinterpret_cast<const u32x4_t*>(bp + i * kFragElems);
         };
         // `live` is false for the steps past the last k-block of a partly filled round: their token
         // fragments are replaced by zeros, so the loop needs no branches.
@@ -182,12 +174,14 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
         for (int s0 = 0; s0 < nkb; s0 += D) {
 #pragma unroll
             for (int i = 0; i < D; ++i) {
+                // the scheduling barriers pin "fetch the block D-1 ahead, then use the oldest": left alone,
+                // the compiler sinks the loads to their first use
                 load(st[(i + D - 1) % D], s0 + i + D - 1);
-                arrived(st[i]);
+                __builtin_amdgcn_sched_barrier(0);
                 mma(st[i], s0 + i < nkb);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the loads fetched ahead past the end
     }
 
     // ---- sum of the four partial tiles, always as (w0 + w2) + (w1 + w3) ------------------------------
