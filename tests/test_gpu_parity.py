@@ -64,6 +64,54 @@ def test_gate_logits(dtype, T, d, E, bias):
     assert err <= U.LOGIT_RTOL * np.max(np.abs(ref)), err
 
 
+# ------------------------------------------------------------------ the whole gate from tokens
+
+# >= 2048 bf16 tokens with d % 32 == 0 and E <= 128 take the fused kernel (logits + top-k + tile ranks), fewer
+# tokens the split one (logits over expert groups, then routing), everything else the fp32-MFMA logits kernel.
+# dup: two pairs of experts get identical weight columns, so their logits tie exactly for every token.
+@pytest.mark.parametrize("dtype,T,d,E,k,C,bias,dup", [
+    ("bf16", 2048, 64, 128, 1, 20, False, False), ("bf16", 2085, 96, 48, 2, 100, True, False),
+    ("bf16", 4096, 32, 8, 2, 600, True, True), ("bf16", 3000, 256, 64, 1, 40, False, True),
+    ("bf16", 2500, 128, 20, 2, 300, True, False), ("bf16", 2111, 64, 30, 1, 64, True, True),
+    ("bf16", 16448, 64, 16, 1, 1100, False, False), ("bf16", 16500, 32, 100, 2, 250, True, True),
+    ("bf16", 77, 2048, 128, 1, 1, True, False), ("bf16", 1000, 64, 30, 2, 50, True, True),
+    ("bf16", 300, 520, 64, 1, 5, False, False), ("bf16", 500, 64, 200, 2, 4, False, True),
+    ("f32", 300, 100, 12, 2, 40, True, True)])
+def test_gate_from_tokens(dtype, T, d, E, k, C, bias, dup):
+    m = U.amd()
+    g = torch.Generator(device=DEV).manual_seed(T + 3 * d + 7 * E)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = torch.randn((T, d), generator=g, device=DEV).to(tdt)
+    Wg = 0.05 * torch.randn((d, E), generator=g, device=DEV)
+    if dup:
+        Wg[:, E - 1] = Wg[:, 1]
+        Wg[:, E // 2] = Wg[:, 0]
+    bg = None
+    if bias:
+        bg = 0.3 * torch.randn((E,), generator=g, device=DEV)
+        if dup:
+            bg[E - 1] = bg[1]
+            bg[E // 2] = bg[0]
+    shape = m.make_shape(T, d, 8, E, k, C, dtype)
+    ws = m.alloc_workspace(shape, DEV)
+    i32 = torch.int32
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device=DEV)
+    r = dict(expert_idx=torch.full((T, k), -7, dtype=i32, device=DEV), slot_idx=torch.full((T, k), -7, dtype=i32, device=DEV),
+             gate_w=torch.full((T, k), -7.0, dtype=torch.float32, device=DEV),
+             expert_rows=torch.full((E,), -7, dtype=i32, device=DEV), slot_token=torch.full((E, C), -7, dtype=i32, device=DEV))
+    for rep in range(2):            # twice on one workspace: nothing may depend on what the previous call left
+        m.moe_gate(shape, x, Wg, bg, logits, r["expert_idx"], r["slot_idx"], r["gate_w"], r["expert_rows"],
+                   r["slot_token"], ws)
+    torch.cuda.synchronize()
+    lg = logits.cpu().numpy()
+    ref_l = orc.gate_logits(x.float().cpu().numpy(), Wg.cpu().numpy(), None if bg is None else bg.cpu().numpy())
+    err = np.max(np.abs(lg.astype(np.float64) - ref_l))
+    assert err <= U.LOGIT_RTOL * np.max(np.abs(ref_l)), err
+    if dup:                         # the tie is exact on the GPU too, and the lower index wins
+        assert np.array_equal(lg[:, E - 1], lg[:, 1]) and np.array_equal(lg[:, E // 2], lg[:, 0])
+    U.assert_routing_equal(r, orc.gate(lg, k, C))     # routing bit-exact on the GPU's own fp32 logits
+
+
 # ------------------------------------------------------------------ dispatch / ffn / combine
 
 def _routing_on_device(ref, dev=DEV):
