@@ -41,20 +41,25 @@ __device__ __forceinline__ int a_swizzle(int row) { return (0x78 >> (((row >> 2)
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 // NWM waves along the rows x 2 along the columns; each owns WM rows x 128 columns
-template <int WM, int NWM> struct TileCfg {
+template <int WM, int NWM, int NS_> struct TileCfg {
     static constexpr int NWAVES = NWM * 2;
     static constexpr int BM = NWM * WM;
     static constexpr int A_BYTES = BM * 64;                    // activation bytes per stage
     static constexpr int STAGE = A_BYTES + kTBBytes;
-    static constexpr int NS = BM == 256 ? 4 : 5;               // stages: 4 x 32 KB or 5 x 24 KB
+    // 256-row tiles: 4 stages of 32 KB, one work-group of 8 waves per CU.  128-row tiles: 5 stages of 24 KB and one
+    // work-group of 4 waves per CU, or 3 stages and at most 256 registers per lane, so that two work-groups share a
+    // CU and one multiplies while the other waits at its barrier: much faster for short K (8192 x 1024 x 4096:
+    // 92 against 141 us), slightly slower for long K, where the deeper ring counts.
+    static constexpr int NS = NS_;
+    static constexpr int WGS_PER_CU = NS_ * (NWM * WM * 64 + kTBBytes) + NWM * WM * 8 <= 80 * 1024 ? 2 : 1;
     static constexpr int NIA = A_BYTES / 1024 / NWAVES;        // activation loads per wave and stage
     static constexpr int NIB = kTBBytes / 1024 / NWAVES;       // weight loads per wave and stage
     static constexpr int LDS_BYTES = NS * STAGE + BM * 8;
 };
 
-template <int WM, int NWM, int EPI>
-__global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
-    typedef TileCfg<WM, NWM> Cfg;
+template <int WM, int NWM, int NSX, int EPI>
+__global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
+    typedef TileCfg<WM, NWM, NSX> Cfg;
     constexpr int BM = Cfg::BM, MSUB = WM / 16, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE, NS = Cfg::NS;
     constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB, NTHREADS = NWM * 128;
     constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
@@ -212,21 +217,21 @@ __global__ __launch_bounds__(NWM * 128) void tgemm_kernel(const WsGemmArgs a) {
     else run(std::integral_constant<int, 1>());
 }
 
-template <int WM, int NWM, int EPI>
+template <int WM, int NWM, int NSX, int EPI>
 static int launch_t(const WsGemmArgs& a, hipStream_t s) {
     constexpr int BM = NWM * WM;
     const int n_tiles = (a.N + kTBN - 1) / kTBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
-    const size_t smem = TileCfg<WM, NWM>::LDS_BYTES;
+    const size_t smem = TileCfg<WM, NWM, NSX>::LDS_BYTES;
     static bool attr_set = false;            // one flag per instantiation
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, NSX, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, EPI>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
+    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -234,7 +239,8 @@ template <int EPI>
 static int launch_t_epi(const WsGemmArgs& a, int WM, hipStream_t s) {
     // 128 x 256 tiles: 2 x 2 waves; 256 x 256 tiles: 4 x 2 waves (64 rows per wave keep the accumulators at 128
     // registers, which the compiler updates in place; 128 rows per wave fill the file and cost copies)
-    return WM == 64 ? launch_t<64, 2, EPI>(a, s) : launch_t<64, 4, EPI>(a, s);
+    if (WM != 64) return launch_t<64, 4, 4, EPI>(a, s);
+    return a.K <= 2048 ? launch_t<64, 2, 3, EPI>(a, s) : launch_t<64, 2, 5, EPI>(a, s);
 }
 
 // 128 rows per wave (256 x 256 tiles) when that still gives every CU a tile, else 64 (128 x 256)
