@@ -217,6 +217,23 @@ def test_layer_reduced(name, bias_std):
     print(name, stats, flush=True)
 
 
+# >= 2048 bf16 tokens: the layer's gate runs as the fused kernel (logits + top-k + tile ranks); narrow models keep
+# the fp64 oracle fast
+WIDE = {
+    "c2w": CONFIGS["c2"].scaled(name="c2w", T=2500, d_model=128, d_ffn=256, E=40, capacity_factor=1.0),
+    "c3w": CONFIGS["c3a"].scaled(name="c3w", T=2100, d_model=64, d_ffn=128, E=16),
+    "c5w": CONFIGS["c5"].scaled(name="c5w", T=2300, d_model=96, d_ffn=160, E=24),
+    "c5x": CONFIGS["c5"].scaled(name="c5x", T=16400, d_model=32, d_ffn=64, E=8),
+}
+
+
+@pytest.mark.parametrize("name", sorted(WIDE))
+def test_layer_fused_gate(name):
+    print(f"case {name}", flush=True)
+    stats = U.check_layer(make_inputs(WIDE[name], DEV, bias_std=0.05))
+    print(name, stats, flush=True)
+
+
 def test_layer_ragged_sizes():
     cfg = CONFIGS["c2"].scaled(name="ragged", T=333, d_model=264, d_ffn=520, E=5, top_k=2, capacity_factor=0.9)
     U.check_layer(make_inputs(cfg, DEV, bias_std=0.05))
