@@ -20,7 +20,7 @@ DEV = "cuda"
 @pytest.mark.parametrize("k,E,C,T", [
     (1, 8, 32, 256), (1, 128, 64, 8192), (1, 128, 1, 64), (2, 64, 640, 16384),
     (1, 1, 5, 9), (2, 2, 3, 10), (1, 3, 7, 63), (2, 3, 7, 65), (1, 64, 3, 257), (2, 128, 2, 1000),
-    (1, 200, 4, 777), (2, 1024, 1, 300), (1, 32, 256, 8192), (2, 8, 100000, 513),
+    (1, 200, 4, 777), (2, 1024, 1, 300), (1, 32, 256, 8192), (2, 8, 100000, 513), (1, 4, 2, 1), (2, 5, 1, 2),
 ])
 def test_gate_routing_bit_exact(kind, k, E, C, T):
     print(f"case kind={kind} k={k} E={E} C={C} T={T}", flush=True)
@@ -68,9 +68,11 @@ def test_gate_logits(dtype, T, d, E, bias):
 
 # >= 2048 bf16 tokens with d % 32 == 0 and E <= 128 take the fused kernel (logits + top-k + tile ranks), fewer
 # tokens the split one (logits over expert groups, then routing), everything else the fp32-MFMA logits kernel.
-# dup: two pairs of experts get identical weight columns, so their logits tie exactly for every token.
+# dup: two pairs of experts get identical weight columns, so their logits tie exactly for every token;
+# "hot": in addition all tokens are equal, so every token makes the same choice.
 @pytest.mark.parametrize("dtype,T,d,E,k,C,bias,dup", [
-    ("bf16", 2048, 64, 128, 1, 20, False, False), ("bf16", 2085, 96, 48, 2, 100, True, False),
+    ("bf16", 2048, 64, 128, 1, 20, False, False), ("bf16", 3001, 64, 16, 2, 37, True, "hot"),
+    ("bf16", 20000, 32, 128, 1, 5000, False, "hot"), ("bf16", 1, 32, 4, 1, 1, True, False), ("bf16", 2085, 96, 48, 2, 100, True, False),
     ("bf16", 4096, 32, 8, 2, 600, True, True), ("bf16", 3000, 256, 64, 1, 40, False, True),
     ("bf16", 2500, 128, 20, 2, 300, True, False), ("bf16", 2111, 64, 30, 1, 64, True, True),
     ("bf16", 16448, 64, 16, 1, 1100, False, False), ("bf16", 16500, 32, 100, 2, 250, True, True),
@@ -82,6 +84,8 @@ def test_gate_from_tokens(dtype, T, d, E, k, C, bias, dup):
     g = torch.Generator(device=DEV).manual_seed(T + 3 * d + 7 * E)
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     x = torch.randn((T, d), generator=g, device=DEV).to(tdt)
+    if dup == "hot":                # every token is the same row: one expert (pair) takes them all
+        x = x[:1].repeat(T, 1).contiguous()
     Wg = 0.05 * torch.randn((d, E), generator=g, device=DEV)
     if dup:
         Wg[:, E - 1] = Wg[:, 1]
