@@ -31,17 +31,20 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return static_cast<uint16_t>(u >> 16);
 }
+// two fp32 -> packed bf16, round to nearest even, on the hardware converter (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const bf16x2_t v = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
+    return __builtin_bit_cast(uint32_t, v);
 }
 
-// gelu_tanh(z) = 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))), with
-// tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 / rcp units.
+// gelu_tanh(z) = 0.5 z (1 + tanh(u)), u = sqrt(2/pi) (z + 0.044715 z^3).  Since tanh(u) = 2 sigmoid(2u) - 1 this is
+// z sigmoid(2u) = z / (1 + exp(-2u)): one exp2 and one rcp on the hardware units, five multiply-adds.
 __device__ __forceinline__ float gelu_tanh(float z) {
-    const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    const float t = __builtin_amdgcn_exp2f(u * 2.8853900817779268f);   // exp(2u)
-    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f);
-    return 0.5f * z * (1.0f + th);
+    const float z2 = z * z;
+    // -2u log2(e) = z (c1 + c3 z^2)
+    const float e = __builtin_amdgcn_exp2f(z * fmaf(z2, -0.10294324f, -2.3022082f));
+    return z * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 template <typename T> struct Elem;
