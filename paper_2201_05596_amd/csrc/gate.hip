@@ -241,13 +241,10 @@ int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* b
 // scratch layout: hist[block][choice][E]
 // ------------------------------------------------------------------------------------------
 template <int K, int NV>
-__global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* __restrict__ logits, int T, int E,
-                                                                   int32_t* __restrict__ expert_idx,
-                                                                   int32_t* __restrict__ slot_idx,
-                                                                   float* __restrict__ gate_w,
-                                                                   int32_t* __restrict__ hist) {
+__device__ __forceinline__ void route_local_body(int32_t* smem, const float* __restrict__ logits, int T, int E,
+                                                 int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot_idx,
+                                                 float* __restrict__ gate_w, int32_t* __restrict__ hist) {
     constexpr int NW = kRouteTokens / kWave;
-    extern __shared__ int32_t smem[];
     int32_t* e_sh = smem;                          // [K][256] chosen expert per token of the block
     int32_t* whist = smem + K * kRouteTokens;      // [NW][K][E]
 
@@ -280,14 +277,23 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
         if (NV > 0) {
             constexpr int NVV = NV > 0 ? NV : 1;
             float v[ROUNDS][NVV];
+            const int live_rounds = min(ROUNDS, (T - tb + 15) / 16);      // rounds that hold a token (uniform over the block)
 #pragma unroll
             for (int it = 0; it < ROUNDS; ++it) {
+                if (it >= live_rounds) break;
                 const float* row = logits + (size_t)min(tb + it * 16 + grp, T - 1) * E;   // clamped: lanes stay in the shuffles
 #pragma unroll
                 for (int i = 0; i < NVV; ++i) v[it][i] = row[min(sub + 16 * i, E - 1)];
             }
 #pragma unroll
             for (int it = 0; it < ROUNDS; ++it) {
+                if (it >= live_rounds) {                                   // no token: only the table entries
+                    if (sub == 0) {
+                        e_sh[it * 16 + grp] = -1;
+                        if (K == 2) e_sh[kRouteTokens + it * 16 + grp] = -1;
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int i = 0; i < NVV; ++i) v[it][i] = sub + 16 * i < E ? v[it][i] : -INFINITY;
                 Best g1, g2;
@@ -336,6 +342,16 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
         for (int j = 0; j < K; ++j)
             slot_idx[(size_t)t * K + j] = my_rank[j] + whist[(w * K + j) * E + my_e[j]];
     }
+}
+
+template <int K, int NV>
+__global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* __restrict__ logits, int T, int E,
+                                                                   int32_t* __restrict__ expert_idx,
+                                                                   int32_t* __restrict__ slot_idx,
+                                                                   float* __restrict__ gate_w,
+                                                                   int32_t* __restrict__ hist) {
+    extern __shared__ int32_t smem[];
+    route_local_body<K, NV>(smem, logits, T, E, expert_idx, slot_idx, gate_w, hist);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -402,15 +418,11 @@ int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order
 // hist holds one histogram [K][E] per block of TB tokens (TB divides 256), coarse one per 256 tokens
 // (the sum of its 256/TB fine ones; the same array when TB is 256).  A work-group finalises 256 tokens.
 template <int K>
-__global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int E, int C, int nblocks, int TB,
-                                                                      const int32_t* __restrict__ expert_idx,
-                                                                      int32_t* __restrict__ slot_idx,
-                                                                      int32_t* __restrict__ expert_rows,
-                                                                      int32_t* __restrict__ slot_token,
-                                                                      int32_t* __restrict__ expert_order,
-                                                                      const int32_t* __restrict__ hist,
-                                                                      const int32_t* __restrict__ coarse) {
-    extern __shared__ int32_t smem[];
+__device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E, int C, int nblocks, int TB,
+                                                    const int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot_idx,
+                                                    int32_t* __restrict__ expert_rows, int32_t* __restrict__ slot_token,
+                                                    int32_t* __restrict__ expert_order, const int32_t* __restrict__ hist,
+                                                    const int32_t* __restrict__ coarse) {
     const int ncol = K * E;                                // column = (choice j, expert e)
     const int q = kRouteTokens / TB;                       // fine blocks per work-group
     int32_t* base = smem;                                  // [q][K][E] rows before the fine block's tokens
@@ -494,6 +506,40 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
     }
 }
 
+template <int K>
+__global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int E, int C, int nblocks, int TB,
+                                                                      const int32_t* __restrict__ expert_idx,
+                                                                      int32_t* __restrict__ slot_idx,
+                                                                      int32_t* __restrict__ expert_rows,
+                                                                      int32_t* __restrict__ slot_token,
+                                                                      int32_t* __restrict__ expert_order,
+                                                                      const int32_t* __restrict__ hist,
+                                                                      const int32_t* __restrict__ coarse) {
+    extern __shared__ int32_t smem[];
+    route_finalize_body<K>(smem, T, E, C, nblocks, TB, expert_idx, slot_idx, expert_rows, slot_token, expert_order, hist,
+                           coarse);
+}
+
+// At most 256 tokens: one block, whose local ranks are already global ones -- both routing kernels in one
+// launch.  What the first half wrote to global memory (chosen experts, ranks, the histogram) is read back by
+// other threads of the same block after the barrier.
+template <int K, int NV>
+__global__ __launch_bounds__(kRouteTokens) void route_single_kernel(const float* __restrict__ logits, int T, int E, int C,
+                                                                    int32_t* __restrict__ expert_idx,
+                                                                    int32_t* __restrict__ slot_idx,
+                                                                    float* __restrict__ gate_w,
+                                                                    int32_t* __restrict__ expert_rows,
+                                                                    int32_t* __restrict__ slot_token,
+                                                                    int32_t* __restrict__ expert_order,
+                                                                    int32_t* __restrict__ hist) {
+    extern __shared__ int32_t smem[];
+    route_local_body<K, NV>(smem, logits, T, E, expert_idx, slot_idx, gate_w, hist);
+    __threadfence_block();
+    __syncthreads();
+    route_finalize_body<K>(smem, T, E, C, 1, kRouteTokens, expert_idx, slot_idx, expert_rows, slot_token, expert_order, hist,
+                           hist);
+}
+
 size_t route_finalize_lds_bytes(int E, int k, int TB) {
     const int ncol = k * E;
     const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
@@ -528,6 +574,28 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const int NW = kRouteTokens / kWave;
     const size_t sm1 = sizeof(int32_t) * ((size_t)k * kRouteTokens + (size_t)NW * k * E);
+    if (nb == 1) {
+        const size_t sm2 = route_finalize_lds_bytes(E, k, kRouteTokens);
+        const size_t sm = sm1 > sm2 ? sm1 : sm2;
+#define MOE_ROUTE_SINGLE(K, NV)                                                                                      \
+    hipLaunchKernelGGL((route_single_kernel<K, NV>), dim3(1), dim3(kRouteTokens), sm, s, logits, T, E, C, expert_idx, \
+                       slot_idx, gate_w, expert_rows, slot_token, expert_order, scratch)
+        if (k == 1) {
+            if (E <= 16) MOE_ROUTE_SINGLE(1, 1);
+            else if (E <= 32) MOE_ROUTE_SINGLE(1, 2);
+            else if (E <= 64) MOE_ROUTE_SINGLE(1, 4);
+            else if (E <= 128) MOE_ROUTE_SINGLE(1, 8);
+            else MOE_ROUTE_SINGLE(1, 0);
+        } else {
+            if (E <= 16) MOE_ROUTE_SINGLE(2, 1);
+            else if (E <= 32) MOE_ROUTE_SINGLE(2, 2);
+            else if (E <= 64) MOE_ROUTE_SINGLE(2, 4);
+            else if (E <= 128) MOE_ROUTE_SINGLE(2, 8);
+            else MOE_ROUTE_SINGLE(2, 0);
+        }
+#undef MOE_ROUTE_SINGLE
+        return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    }
 #define MOE_ROUTE_LOCAL(K, NV)                                                                                   \
     hipLaunchKernelGGL((route_local_kernel<K, NV>), dim3(nb), dim3(kRouteTokens), sm1, s, logits, T, E, expert_idx, \
                        slot_idx, gate_w, scratch)
