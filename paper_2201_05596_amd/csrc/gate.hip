@@ -415,7 +415,9 @@ int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-// hist holds one histogram [K][E] per block of TB tokens (TB divides 256), coarse one per 256 tokens
+constexpr int kMaxFine = 8;      // fine blocks per 256 tokens at most (32-token tiles)
+
+// hist holds one histogram [K][E] per block of TB tokens (TB divides 256, TB >= 32), coarse one per 256 tokens
 // (the sum of its 256/TB fine ones; the same array when TB is 256).  A work-group finalises 256 tokens.
 template <int K>
 __device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E, int C, int nblocks, int TB,
@@ -465,11 +467,21 @@ __device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E,
             run[1] = tot[0] + pre[1];
             total += tot[1];
         }
-        for (int f = 0; f < q; ++f) {
+        // the fine histograms of this block, fetched together (one memory round trip, not one per fine block)
+        int fine[kMaxFine - 1][K];
 #pragma unroll
-            for (int j = 0; j < K; ++j) {
-                base[(f * K + j) * E + e] = run[j];
-                if (f + 1 < q && (b * q + f) * TB < T) run[j] += hist[((size_t)(b * q + f) * K + j) * E + e];
+        for (int f = 0; f < kMaxFine - 1; ++f)
+#pragma unroll
+            for (int j = 0; j < K; ++j)
+                fine[f][j] = (f + 1 < q && (b * q + f) * TB < T) ? hist[((size_t)(b * q + f) * K + j) * E + e] : 0;
+#pragma unroll
+        for (int f = 0; f < kMaxFine; ++f) {
+            if (f < q) {
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    base[(f * K + j) * E + e] = run[j];
+                    if (f < kMaxFine - 1) run[j] += fine[f < kMaxFine - 1 ? f : 0][j];
+                }
             }
         }
         rows_sh[e] = min(total, C);
