@@ -212,8 +212,7 @@ static int launch_logits_t(const XT* x, const float* Wg, const float* bg, float*
                                logits, T, d, E);                                                             \
     } while (0)
     const bool wide = E > 64;          // 128 experts per pass, else 64
-    const char* tune_env = getenv("MOE_TUNE_LOGITS_FEW");
-    const bool few = tune_env ? atoi(tune_env) != 0 : T <= 1024;   // few tokens: waves go to k-splits, not token tiles
+    const bool few = T <= 1024;        // few tokens: waves go to k-splits, not token tiles
     if (wide) {
         if (few) MOE_LOGITS_CASE(1, 2, 2);
         else MOE_LOGITS_CASE(2, 2, 1);
