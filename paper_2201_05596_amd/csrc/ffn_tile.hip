@@ -54,18 +54,25 @@ template <int WM, int NWM, int NS_> struct TileCfg {
     static constexpr int WGS_PER_CU = NS_ * (NWM * WM * 64 + kTBBytes) + NWM * WM * 8 <= 80 * 1024 ? 2 : 1;
     static constexpr int NIA = A_BYTES / 1024 / NWAVES;        // activation loads per wave and stage
     static constexpr int NIB = kTBBytes / 1024 / NWAVES;       // weight loads per wave and stage
-    static constexpr int LDS_BYTES = NS * STAGE + BM * 8;
+    // Tiles of 256 rows that hold at most 128 valid ones (lightly loaded experts, the last rows of a busy one) need
+    // only half of the activation space; the ring is then cut into 6 stages of 24 KB instead of 4 of 32 KB, which
+    // keeps 80 KB of weights in flight instead of 48 KB: such tiles are bound by the rate one CU can stream at.
+    static constexpr bool HAS_LIGHT = NWM == 4;
+    static constexpr int L_ROWS = NWAVES * 16;                 // one activation load per wave and stage
+    static constexpr int L_A_BYTES = L_ROWS * 64;
+    static constexpr int L_STAGE = L_A_BYTES + kTBBytes;
+    static constexpr int L_NS = 6;
+    static constexpr int RING = HAS_LIGHT && L_NS * L_STAGE > NS * STAGE ? L_NS * L_STAGE : NS * STAGE;
+    static constexpr int LDS_BYTES = RING + BM * 8;
 };
 
 template <int WM, int NWM, int NSX, int EPI>
 __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
     typedef TileCfg<WM, NWM, NSX> Cfg;
-    constexpr int BM = Cfg::BM, MSUB = WM / 16, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE, NS = Cfg::NS;
-    constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB, NTHREADS = NWM * 128;
-    constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
+    constexpr int BM = Cfg::BM, MSUB = WM / 16, NIB = Cfg::NIB, NTHREADS = NWM * 128;
 
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // NS stages, then BM row indices
-    long long* arow_sh = reinterpret_cast<long long*>(lds + NS * STAGE);
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // the ring of stages, then BM row indices
+    long long* arow_sh = reinterpret_cast<long long*>(lds + Cfg::RING);
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));   // LDS byte offset of the segment
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -89,6 +96,21 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
         arow_sh[i] = a.row_map ? (long long)a.row_map[(size_t)g * a.map_stride + r] : (long long)g * a.a_group_stride + r;
     }
     __syncthreads();
+
+    // The rest of the kernel exists once per number ACT of 16-row sub-tiles that a wave works on:
+    // a tile of a lightly loaded expert is pure weight streaming and must not pay matrix-core time
+    // (or LDS reads) for rows that do not exist.  The choice is wave-uniform; a wave without valid rows
+    // still takes part in the loads and barriers.  Separate copies (not branches inside one loop) keep
+    // the accumulators of each copy in place in the register file.
+    // A wave without valid rows (ACT = 0) still takes part in the loads and barriers, nothing else.
+    const int nsub = __builtin_amdgcn_readfirstlane(max(0, (min(nrows - wm * WM, WM) + 15) / 16));
+    auto run = [&](auto act_c, auto light_c) {
+    constexpr int ACT = decltype(act_c)::value;
+    constexpr bool LIGHT = decltype(light_c)::value;
+    constexpr int NA = ACT > 0 ? ACT : 1;                       // array extents
+    constexpr int NS = LIGHT ? Cfg::L_NS : Cfg::NS, STAGE = LIGHT ? Cfg::L_STAGE : Cfg::STAGE;
+    constexpr int A_BYTES = LIGHT ? Cfg::L_A_BYTES : Cfg::A_BYTES, NIA = LIGHT ? 1 : Cfg::NIA;
+    constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
 
     // ---- per-lane sources of the direct loads (fixed for the whole k-loop) ---------------------------
     // activations: wave w, load i copies rows (w*NIA + i)*16 .. +15; lane L -> row +L/4, slot L%4
@@ -119,17 +141,9 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
             dma16(bp + i * b_step2, __builtin_amdgcn_readfirstlane(base + A_BYTES + (w * NIB + i) * 1024));
     };
 
-    // The rest of the kernel exists once per number ACT of 16-row sub-tiles that a wave works on:
-    // a tile of a lightly loaded expert is pure weight streaming and must not pay matrix-core time
-    // (or LDS reads) for rows that do not exist.  The choice is wave-uniform; a wave without valid rows
-    // still takes part in the loads and barriers.  Separate copies (not branches inside one loop) keep
-    // the accumulators of each copy in place in the register file.
-    const int nsub = __builtin_amdgcn_readfirstlane((min(nrows - wm * WM, WM) + 15) / 16);
-    auto run = [&](auto act_c) {
-    constexpr int ACT = decltype(act_c)::value;
-    f32x4_t acc[ACT][8];
+    f32x4_t acc[NA][8];
 #pragma unroll
-    for (int i = 0; i < ACT; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -141,9 +155,10 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
     // operand fragments of one stage in registers
     struct Frags {
         uint4 braw[8];
-        bf16x8_t af[ACT];
+        bf16x8_t af[NA];
     };
     auto read_frags = [&](Frags& f, int buf) {
+        if (ACT == 0) return;
         const char* base = lds + buf * STAGE;
 #pragma unroll
         for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
@@ -151,6 +166,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
         for (int ms = 0; ms < ACT; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
     };
     auto mma = [&](const Frags& f) {
+        if (ACT == 0) return;
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
             bf16x8_t blo, bhi;
@@ -192,7 +208,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
 
     // ---- epilogue ------------------------------------------------------------------------------
     const int n_lane = n0 + wn * 128 + c * 8;
-        if (n_lane >= a.N) return;
+    if (ACT == 0 || n_lane >= a.N) return;
     float bias[8];
     load_bias8(a, g, n_lane, bias);
 #pragma unroll
@@ -212,9 +228,19 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
         __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
     }
     };
-    if (nsub > 2) run(std::integral_constant<int, MSUB>());
-    else if (nsub == 2) run(std::integral_constant<int, 2>());
-    else run(std::integral_constant<int, 1>());
+    typedef std::integral_constant<bool, false> Full;
+    typedef std::integral_constant<bool, Cfg::HAS_LIGHT> Light;
+    if (Cfg::HAS_LIGHT && nrows <= Cfg::L_ROWS) {               // uniform over the work-group
+        if (nsub > 2) run(std::integral_constant<int, MSUB>(), Light());
+        else if (nsub == 2) run(std::integral_constant<int, 2>(), Light());
+        else if (nsub == 1) run(std::integral_constant<int, 1>(), Light());
+        else run(std::integral_constant<int, 0>(), Light());
+    } else {
+        if (nsub > 2) run(std::integral_constant<int, MSUB>(), Full());
+        else if (nsub == 2) run(std::integral_constant<int, 2>(), Full());
+        else if (nsub == 1) run(std::integral_constant<int, 1>(), Full());
+        else run(std::integral_constant<int, 0>(), Full());
+    }
 }
 
 template <int WM, int NWM, int NSX, int EPI>
