@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--config", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--capacity-factor", type=float, default=None, help="experiment: override the workload's capacity factor")
+    ap.add_argument("--no-gate-bias", action="store_true",
+                    help="experiment: drop the workload's gate bias (c5 without its skew: ~512 rows per expert)")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="experiment: time the steps without the library's per-stage events (no roofline then)")
     ap.add_argument("--all-stage-events", action="store_true", help="time every stage (more events, slower step)")
@@ -111,6 +113,8 @@ def main() -> int:
     cfg = CONFIGS[args.config]
     if args.capacity_factor is not None:
         cfg = cfg.scaled(name=f"{cfg.name}-cf{args.capacity_factor}", capacity_factor=args.capacity_factor)
+    if args.no_gate_bias:
+        cfg = cfg.scaled(name=f"{cfg.name}-nobias", gate_bias_zipf=None)
     inp = make_inputs(cfg, "cuda:0")
     layer = moe.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, cfg.capacity, cfg.dtype, inp.Wg, inp.bg,
                          inp.W1, inp.b1, inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)
