@@ -40,217 +40,244 @@ struct WsWork {
     int vb, g, nt, m0, nrows, ch_beg, ch_end;
 };
 
+// Compile-time shape of a tile and what follows from it
+template <int MT, int NW> struct WsTile {
+    static constexpr int NT = NW * 64;
+    static constexpr int MSUB = MT / 16;
+    static constexpr int KC = kLdsTileElems / MT;        // k-extent of one LDS chunk
+    static constexpr int STRIDE = KC * 2 + 16;           // bytes per LDS row
+    static constexpr int PIECES = MT * KC / 8;           // 16-byte pieces per chunk
+    static constexpr int NP = PIECES / NT;               // pieces per thread
+    static constexpr int SFC = KC / kSF;                 // super-fragments per chunk
+    static constexpr int LDS_A = 2 * MT * STRIDE;        // the two activation buffers
+    static_assert(PIECES % NT == 0 && SFC >= 1, "tile configuration");
+};
+
+// Tile counts of one GEMM (uniform over the grid)
+struct WsGeo {
+    int n_tiles, m_tiles, inner_n, chunks_total, chunks_per;
+};
+template <int MT, int NW> __device__ __forceinline__ WsGeo ws_geo(const WsGemmArgs& a) {
+    WsGeo g;
+    g.n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
+    g.m_tiles = (a.max_rows + MT - 1) / MT;
+    g.inner_n = g.m_tiles * a.ksplit;
+    g.chunks_total = (a.K + WsTile<MT, NW>::KC - 1) / WsTile<MT, NW>::KC;
+    g.chunks_per = (g.chunks_total + a.ksplit - 1) / a.ksplit;     // whole chunks per k-split
+    return g;
+}
+
+// The first virtual block vb, vb + stride, ... below `limit` that has work, as a tile; t.vb >= limit if none.
+// Uniform over the work-group.
+template <int MT, int EPI>
+__device__ __forceinline__ WsWork ws_find_work(const WsGemmArgs& a, const WsGeo& geo, int vb, int limit, int stride) {
+    WsWork t{};
+    for (; vb < limit; vb += stride) {
+        const TileId tile = tile_of_block(a, geo.n_tiles, geo.inner_n, vb);
+        if (!tile.live) continue;
+        const int rows = a.rows ? min(a.rows[tile.g], a.max_rows) : a.fixed_rows;
+        const int mt = tile.inner % geo.m_tiles, ks = tile.inner / geo.m_tiles;
+        if (mt * MT >= rows) continue;
+        t.ch_beg = ks * geo.chunks_per;
+        t.ch_end = min(t.ch_beg + geo.chunks_per, geo.chunks_total);
+        if (t.ch_beg >= t.ch_end && EPI != EPI_PARTIAL) continue;
+        t.g = tile.g; t.nt = tile.nt; t.m0 = mt * MT; t.nrows = min(MT, rows - t.m0);
+        break;
+    }
+    t.vb = vb;
+    return t;
+}
+
+// One tile: prologue (row table, first activation chunk), the weight stream down K, epilogue.  `nxt` is the
+// work-group's next tile OF THE SAME GEMM (has_next false if there is none): the fragments fetched ahead at the
+// end of this tile are its first ones, and `primed` tells the next call that they are in `raw` already.
 template <int MT, int NW, int EPI, int NBUF>
-__global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, const int total_blocks) {
-    constexpr int NT = NW * 64;
-    constexpr int MSUB = MT / 16;
-    constexpr int KC = kLdsTileElems / MT;        // k-extent of one LDS chunk
-    constexpr int STRIDE = KC * 2 + 16;           // bytes per LDS row
-    constexpr int PIECES = MT * KC / 8;           // 16-byte pieces per chunk
-    constexpr int NP = PIECES / NT;               // pieces per thread
-    constexpr int SFC = KC / kSF;                 // super-fragments per chunk
-    static_assert(PIECES % NT == 0 && SFC >= 1 && SFC % NBUF == 0, "tile configuration");
-
-    __shared__ __attribute__((aligned(16))) char lds[2 * MT * STRIDE];
-    __shared__ long long arow_sh[MT];
-    __shared__ int tok_sh[MT];                     // EPI_SCATTER: token and gate probability of the tile's rows
-    __shared__ float gw_sh[MT];
-
+__device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, const WsWork& cur, const WsWork& nxt,
+                                        const bool has_next, uint4 (&raw)[NBUF][8], bool& primed, char* lds,
+                                        long long* arow_sh, int* tok_sh, float* gw_sh) {
+    typedef WsTile<MT, NW> TC;
+    constexpr int NT = TC::NT, MSUB = TC::MSUB, KC = TC::KC, STRIDE = TC::STRIDE, NP = TC::NP, SFC = TC::SFC;
+    static_assert(SFC % NBUF == 0, "tile configuration");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int c = lane & 15, kg = lane >> 4;
-
-    const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
-    const int m_tiles = (a.max_rows + MT - 1) / MT;
-    const int inner_n = m_tiles * a.ksplit;
-    const int chunks_total = (a.K + KC - 1) / KC;
-    const int chunks_per = (chunks_total + a.ksplit - 1) / a.ksplit;     // whole chunks per k-split
-
-    if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NT);
-
-    // ---- the work-group's tiles ---------------------------------------------------------------
-    // The grid holds as many work-groups as fit on the chip at once; work-group b takes the virtual
-    // blocks b, b + gridDim.x, ... that have work (the XCD of a virtual block is that of b: the grid
-    // is a multiple of the XCD count).  Knowing the next tile early lets the weight stream run on
-    // across tile boundaries.  Everything here is uniform over the work-group.
-    auto find_work = [&](int vb) {
-        WsWork t{};
-        for (; vb < total_blocks; vb += gridDim.x) {
-            const TileId tile = tile_of_block(a, n_tiles, inner_n, vb);
-            if (!tile.live) continue;
-            const int rows = a.rows ? min(a.rows[tile.g], a.max_rows) : a.fixed_rows;
-            const int mt = tile.inner % m_tiles, ks = tile.inner / m_tiles;
-            if (mt * MT >= rows) continue;
-            t.ch_beg = ks * chunks_per;
-            t.ch_end = min(t.ch_beg + chunks_per, chunks_total);
-            if (t.ch_beg >= t.ch_end && EPI != EPI_PARTIAL) continue;
-            t.g = tile.g; t.nt = tile.nt; t.m0 = mt * MT; t.nrows = min(MT, rows - t.m0);
-            break;
-        }
-        t.vb = vb;
-        return t;
-    };
-    // first of the 8 columns of this lane in column tile nt, and whether they exist
+    const int chunks_per = geo.chunks_per;
+    // first of the 8 columns of this lane in column tile nt
     auto lane_col = [&](int nt) { return nt * (NW * kWaveCols) + w * kWaveCols + c * 8; };
-
     int akp[NP];                                   // k-offset of this thread's activation pieces
 #pragma unroll
     for (int i = 0; i < NP; ++i) akp[i] = ((tid + i * NT) % (KC / 8)) * 8;
 
-    uint4 raw[NBUF][8];                            // weight super-fragments in flight
-    bool primed = false;                           // raw[0..NBUF-2] already hold this tile's first fragments
+    const int g = cur.g, m0 = cur.m0, nrows = cur.nrows, ch_beg = cur.ch_beg, ch_end = cur.ch_end;
 
-    WsWork cur = find_work(blockIdx.x);
-    while (cur.vb < total_blocks) {
-        const WsWork nxt = find_work(cur.vb + gridDim.x);
-        const bool has_next = nxt.vb < total_blocks;
-        const int g = cur.g, m0 = cur.m0, nrows = cur.nrows, ch_beg = cur.ch_beg, ch_end = cur.ch_end;
+    // ---- A rows of the tile ----------------------------------------------------------
+    lds_barrier();                                              // the previous tile's readers are done
+    if (tid < MT) {
+        const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
+        long long ar;
+        if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
+        else ar = (long long)g * a.a_group_stride + r;
+        arow_sh[tid] = ar;
+        if (EPI == EPI_SCATTER) scatter_lookup(a, g, r, tok_sh[tid], gw_sh[tid]);
+    }
+    lds_barrier();
 
-        // ---- A rows of the tile ----------------------------------------------------------
-        lds_barrier();                                              // the previous tile's readers are done
-        if (tid < MT) {
-            const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
-            long long ar;
-            if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
-            else ar = (long long)g * a.a_group_stride + r;
-            arow_sh[tid] = ar;
-            if (EPI == EPI_SCATTER) scatter_lookup(a, g, r, tok_sh[tid], gw_sh[tid]);
+    // ---- per-lane weight pointers: 8 columns n_lane..n_lane+7 of rows k, this tile and the next ----
+    const int n_lane_raw = lane_col(cur.nt);
+    const bool col_ok = n_lane_raw < a.N;
+    const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
+    const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
+    // everything the epilogue needs from memory is fetched here: a load issued after the weight
+    // fragments that run ahead into the next tile could only be waited for together with them
+    const uint4 bias_raw = EPI != EPI_PARTIAL ? load_bias_raw(a, g, n_lane) : make_uint4(0, 0, 0, 0);
+    const uint16_t* Bn = a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
+    const int k_end_pad = ch_end * KC;                          // first k that belongs to the next tile
+    const int k_next = has_next ? nxt.ch_beg * KC : 0;
+
+    f32x4_t acc[MSUB][8];
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // activation chunk: global -> registers -> LDS.  Each thread moves NP 16-byte pieces per chunk;
+    // their rows and k-offsets never change, so the row pointers are formed once.  The loads are
+    // unconditional (k clamped into the row, the value replaced by zero past K) so that the main
+    // loop has no branches around memory operations and the prefetches really stay in flight.
+    const uint16_t* arow_ptr[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) arow_ptr[i] = a.A + (size_t)arow_sh[(tid + i * NT) / (KC / 8)] * a.K;
+    uint4 areg[NP];
+    auto a_load = [&](int ch) {                     // loads only: nothing here waits for them
+        const int k0 = ch * KC;
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+            areg[i] = *reinterpret_cast<const uint4*>(arow_ptr[i] + min(k0 + akp[i], a.K - 8));
+    };
+    auto a_store = [&](int ch, int buf) {           // zero past K, then registers -> LDS
+        char* base = lds + buf * MT * STRIDE;
+        const int k0 = ch * KC;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int p = tid + i * NT;
+            const int r = p / (KC / 8), kp = p % (KC / 8);
+            const bool in = k0 + akp[i] < a.K;
+            const uint4 v = areg[i];
+            *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) =
+                make_uint4(in ? v.x : 0u, in ? v.y : 0u, in ? v.z : 0u, in ? v.w : 0u);
         }
-        lds_barrier();
+    };
 
-        // ---- per-lane weight pointers: 8 columns n_lane..n_lane+7 of rows k, this tile and the next ----
-        const int n_lane_raw = lane_col(cur.nt);
-        const bool col_ok = n_lane_raw < a.N;
-        const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
-        const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
-        // everything the epilogue needs from memory is fetched here: a load issued after the weight
-        // fragments that run ahead into the next tile could only be waited for together with them
-        const uint4 bias_raw = EPI != EPI_PARTIAL ? load_bias_raw(a, g, n_lane) : make_uint4(0, 0, 0, 0);
-        const uint16_t* Bn = a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
-        const int k_end_pad = ch_end * KC;                          // first k that belongs to the next tile
-        const int k_next = has_next ? nxt.ch_beg * KC : 0;
-
-        f32x4_t acc[MSUB][8];
+    // weight super-fragment: rows k0 + kg*8 + j, j = 0..7.  K is a multiple of 8: a lane's 8 rows are all
+    // inside or all outside.  Rows in [K, k_end_pad) re-read the last 8 rows (in bounds) and meet zeros on
+    // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
+    // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
+    // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
+    auto b_load = [&](uint4 (&dst)[8], int k0) {
+        const int kk = k0 + kg * 8;
+        const bool own = kk < k_end_pad;
+        const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
 #pragma unroll
-        for (int i = 0; i < MSUB; ++i)
+        for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
+    };
+    auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
+        bf16x8_t af[MSUB];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-        // activation chunk: global -> registers -> LDS.  Each thread moves NP 16-byte pieces per chunk;
-        // their rows and k-offsets never change, so the row pointers are formed once.  The loads are
-        // unconditional (k clamped into the row, the value replaced by zero past K) so that the main
-        // loop has no branches around memory operations and the prefetches really stay in flight.
-        const uint16_t* arow_ptr[NP];
+        for (int ms = 0; ms < MSUB; ++ms)
+            af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
 #pragma unroll
-        for (int i = 0; i < NP; ++i) arow_ptr[i] = a.A + (size_t)arow_sh[(tid + i * NT) / (KC / 8)] * a.K;
-        uint4 areg[NP];
-        auto a_load = [&](int ch) {                     // loads only: nothing here waits for them
-            const int k0 = ch * KC;
-#pragma unroll
-            for (int i = 0; i < NP; ++i)
-                areg[i] = *reinterpret_cast<const uint4*>(arow_ptr[i] + min(k0 + akp[i], a.K - 8));
-        };
-        auto a_store = [&](int ch, int buf) {           // zero past K, then registers -> LDS
-            char* base = lds + buf * MT * STRIDE;
-            const int k0 = ch * KC;
-#pragma unroll
-            for (int i = 0; i < NP; ++i) {
-                const int p = tid + i * NT;
-                const int r = p / (KC / 8), kp = p % (KC / 8);
-                const bool in = k0 + akp[i] < a.K;
-                const uint4 v = areg[i];
-                *reinterpret_cast<uint4*>(base + r * STRIDE + kp * 16) =
-                    make_uint4(in ? v.x : 0u, in ? v.y : 0u, in ? v.z : 0u, in ? v.w : 0u);
-            }
-        };
-
-        // weight super-fragment: rows k0 + kg*8 + j, j = 0..7.  K is a multiple of 8: a lane's 8 rows are all
-        // inside or all outside.  Rows in [K, k_end_pad) re-read the last 8 rows (in bounds) and meet zeros on
-        // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
-        // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
-        // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
-        auto b_load = [&](uint4 (&dst)[8], int k0) {
-            const int kk = k0 + kg * 8;
-            const bool own = kk < k_end_pad;
-            const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
-        };
-        auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
-            bf16x8_t af[MSUB];
-#pragma unroll
-            for (int ms = 0; ms < MSUB; ++ms)
-                af[ms] = *reinterpret_cast<const bf16x8_t*>(a_lane + ms * 16 * STRIDE);
-#pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-                bf16x8_t blo, bhi;
-                b_frag_pair(src, qq, blo, bhi);
-#pragma unroll
-                for (int ms = 0; ms < MSUB; ++ms) {
-                    acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
-                    acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
-                }
-            }
-        };
-
-        if (ch_beg < ch_end) {
-            // prologue: first weight super-fragments in flight (unless the previous tile already
-            // fetched them), first activation chunk in LDS
-            if (!primed) {
-#pragma unroll
-                for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
-            }
-            a_load(ch_beg);
-            a_store(ch_beg, 0);
-            lds_barrier();
-
-            const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
-            for (int ch = ch_beg; ch < ch_end; ++ch) {
-                const int buf = (ch - ch_beg) & 1;
-                a_load(ch + 1);                    // next chunk (past the end: clamped and zeroed, never used)
-                __builtin_amdgcn_sched_barrier(0);
-                const char* a_lane = a_lane0 + buf * MT * STRIDE;
-                const int kbase = ch * KC;
-#pragma unroll
-                for (int s = 0; s < SFC; s += NBUF) {
-#pragma unroll
-                    for (int b = 0; b < NBUF; ++b) {
-                        // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b.
-                        // The scheduling barriers pin that order: left alone, the compiler sinks the loads
-                        // down to their first use and the prefetch distance collapses to zero.
-                        b_load(raw[(b + NBUF - 1) % NBUF], kbase + (s + b + NBUF - 1) * kSF);
-                        __builtin_amdgcn_sched_barrier(0);
-                        sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-                a_store(ch + 1, buf ^ 1);
-                lds_barrier();
-            }
-            primed = has_next;
-        } else {
-            primed = false;
-        }
-
-        // ---- epilogue ------------------------------------------------------------------------
-        if (col_ok) {
-            const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
-            const int ks = ch_beg / chunks_per;
-            float bias[8];
-            unpack_bias8(bias_raw, bias);
+        for (int qq = 0; qq < 4; ++qq) {
+            bf16x8_t blo, bhi;
+            b_frag_pair(src, qq, blo, bhi);
 #pragma unroll
             for (int ms = 0; ms < MSUB; ++ms) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int rl = ms * 16 + mg * 4 + r;
-                    if (rl >= nrows) continue;
-                    float v[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
-                    finish_row<EPI>(a, g, m0 + rl, ks, n_lane, v, EPI == EPI_SCATTER ? tok_sh[rl] : 0,
-                                    EPI == EPI_SCATTER ? gw_sh[rl] : 1.f);
-                }
+                acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
+                acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
             }
         }
+    };
+
+    if (ch_beg < ch_end) {
+        // prologue: first weight super-fragments in flight (unless the previous tile already
+        // fetched them), first activation chunk in LDS
+        if (!primed) {
+#pragma unroll
+            for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
+        }
+        a_load(ch_beg);
+        a_store(ch_beg, 0);
+        lds_barrier();
+
+        const char* a_lane0 = lds + (lane & 15) * STRIDE + kg * 16;
+        for (int ch = ch_beg; ch < ch_end; ++ch) {
+            const int buf = (ch - ch_beg) & 1;
+            a_load(ch + 1);                    // next chunk (past the end: clamped and zeroed, never used)
+            __builtin_amdgcn_sched_barrier(0);
+            const char* a_lane = a_lane0 + buf * MT * STRIDE;
+            const int kbase = ch * KC;
+#pragma unroll
+            for (int s = 0; s < SFC; s += NBUF) {
+#pragma unroll
+                for (int b = 0; b < NBUF; ++b) {
+                    // keep NBUF-1 super-fragments in flight: fetch the one NBUF-1 ahead, then use slot b.
+                    // The scheduling barriers pin that order: left alone, the compiler sinks the loads
+                    // down to their first use and the prefetch distance collapses to zero.
+                    b_load(raw[(b + NBUF - 1) % NBUF], kbase + (s + b + NBUF - 1) * kSF);
+                    __builtin_amdgcn_sched_barrier(0);
+                    sf_compute(raw[b], a_lane + (s + b) * kSF * 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            a_store(ch + 1, buf ^ 1);
+            lds_barrier();
+        }
+        primed = has_next;
+    } else {
+        primed = false;
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------
+    if (col_ok) {
+        const int mg = kg;                                     // D: rows 4*(lane/16)+r, column lane%16
+        const int ks = ch_beg / chunks_per;
+        float bias[8];
+        unpack_bias8(bias_raw, bias);
+#pragma unroll
+        for (int ms = 0; ms < MSUB; ++ms) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int rl = ms * 16 + mg * 4 + r;
+                if (rl >= nrows) continue;
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
+                finish_row<EPI>(a, g, m0 + rl, ks, n_lane, v, EPI == EPI_SCATTER ? tok_sh[rl] : 0,
+                                EPI == EPI_SCATTER ? gw_sh[rl] : 1.f);
+            }
+        }
+    }
+}
+
+template <int MT, int NW, int EPI, int NBUF>
+__global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, const int total_blocks) {
+    typedef WsTile<MT, NW> TC;
+    __shared__ __attribute__((aligned(16))) char lds[TC::LDS_A];
+    __shared__ long long arow_sh[MT];
+    __shared__ int tok_sh[MT];                     // EPI_SCATTER: token and gate probability of the tile's rows
+    __shared__ float gw_sh[MT];
+
+    const WsGeo geo = ws_geo<MT, NW>(a);
+    if (EPI == EPI_SCATTER) zero_dropped_rows(a, threadIdx.x, TC::NT);
+
+    // The grid holds as many work-groups as fit on the chip at once; work-group b takes the virtual
+    // blocks b, b + gridDim.x, ... that have work (the XCD of a virtual block is that of b: the grid
+    // is a multiple of the XCD count).  Knowing the next tile early lets the weight stream run on
+    // across tile boundaries.
+    uint4 raw[NBUF][8];                            // weight super-fragments in flight
+    bool primed = false;                           // raw[0..NBUF-2] already hold the tile's first fragments
+    WsWork cur = ws_find_work<MT, EPI>(a, geo, blockIdx.x, total_blocks, gridDim.x);
+    while (cur.vb < total_blocks) {
+        const WsWork nxt = ws_find_work<MT, EPI>(a, geo, cur.vb + gridDim.x, total_blocks, gridDim.x);
+        ws_tile<MT, NW, EPI, NBUF>(a, geo, cur, nxt, nxt.vb < total_blocks, raw, primed, lds, arow_sh, tok_sh, gw_sh);
         cur = nxt;
     }
 }
