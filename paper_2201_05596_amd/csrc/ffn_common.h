@@ -121,25 +121,27 @@ __device__ __forceinline__ void scatter_lookup(const WsGemmArgs& a, int g, int r
     gw = a.gate_w[(size_t)t * a.top_k];
 }
 
-// Finishes 8 consecutive columns n_lane.. of row `row` (index inside group g): v = acc + bias on entry.
+// Finishes NC (8 or 4) consecutive columns n_lane.. of row `row` (index inside group g): v = acc + bias on entry.
 // EPI_SCATTER: (t, gw) = scatter_lookup of the row, fetched by the caller.
-template <int EPI>
-__device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, int ks, int n_lane, float (&v)[8],
+template <int EPI, int NC = 8>
+__device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, int ks, int n_lane, float (&v)[NC],
                                            int t = 0, float gw = 1.f) {
+    static_assert(NC == 8 || NC == 4, "columns per lane");
     const long long grow = (long long)g * a.o_group_stride + row;   // row in [G, o_group_stride]
     if (EPI == EPI_PARTIAL) {
         float* o = a.partial + ((size_t)ks * a.partial_rows + grow) * a.N + n_lane;
-        *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+        for (int q = 0; q < NC / 4; ++q)
+            *reinterpret_cast<float4*>(o + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
         return;
     }
     size_t orow = (size_t)grow;
     if (EPI == EPI_GELU) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = gelu_tanh(v[i]);
+        for (int i = 0; i < NC; ++i) v[i] = gelu_tanh(v[i]);
     } else if (EPI == EPI_SCATTER) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] *= gw;
+        for (int i = 0; i < NC; ++i) v[i] *= gw;
         orow = (size_t)t;
     } else if (EPI == EPI_COMBINE) {
         // dense branch + sum_j keep_j g_j ye[e_j, slot_j, :] for token grow
@@ -148,21 +150,37 @@ __device__ __forceinline__ void finish_row(const WsGemmArgs& a, int g, int row, 
             if (s < 0) continue;
             const int e = a.expert_idx[grow * a.top_k + j];
             const float gw = a.gate_w[grow * a.top_k + j];
-            const uint4 yv = *reinterpret_cast<const uint4*>(a.ye + ((size_t)e * a.C + s) * a.N + n_lane);
-            v[0] = fmaf(gw, __uint_as_float(yv.x << 16), v[0]); v[1] = fmaf(gw, __uint_as_float(yv.x & 0xffff0000u), v[1]);
-            v[2] = fmaf(gw, __uint_as_float(yv.y << 16), v[2]); v[3] = fmaf(gw, __uint_as_float(yv.y & 0xffff0000u), v[3]);
-            v[4] = fmaf(gw, __uint_as_float(yv.z << 16), v[4]); v[5] = fmaf(gw, __uint_as_float(yv.z & 0xffff0000u), v[5]);
-            v[6] = fmaf(gw, __uint_as_float(yv.w << 16), v[6]); v[7] = fmaf(gw, __uint_as_float(yv.w & 0xffff0000u), v[7]);
+            const uint16_t* yp = a.ye + ((size_t)e * a.C + s) * a.N + n_lane;
+            uint32_t y[NC / 2];
+            if (NC == 8) {
+                const uint4 yv = *reinterpret_cast<const uint4*>(yp);
+                y[0] = yv.x; y[1] = yv.y; y[NC / 2 - 2] = yv.z; y[NC / 2 - 1] = yv.w;
+            } else {
+                const uint2 yv = *reinterpret_cast<const uint2*>(yp);
+                y[0] = yv.x; y[1] = yv.y;
+            }
+#pragma unroll
+            for (int q = 0; q < NC / 2; ++q) {
+                v[2 * q] = fmaf(gw, __uint_as_float(y[q] << 16), v[2 * q]);
+                v[2 * q + 1] = fmaf(gw, __uint_as_float(y[q] & 0xffff0000u), v[2 * q + 1]);
+            }
         }
     }
-    uint4 o;
-    o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
-    o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+    uint32_t o[NC / 2];
+#pragma unroll
+    for (int q = 0; q < NC / 2; ++q) o[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
     // h and the layer output are written once and read much later or never: streaming stores keep them
     // from displacing the activation rows in L2.  Expert outputs and split-K partials are read back at once.
-    uint4* dst = reinterpret_cast<uint4*>(a.out + orow * a.N + n_lane);
-    if (EPI == EPI_STORE) *dst = o;
-    else store_stream16(dst, o);
+    uint16_t* dst = a.out + orow * a.N + n_lane;
+    if (NC == 8) {
+        const uint4 ov = make_uint4(o[0], o[1], o[NC / 2 - 2], o[NC / 2 - 1]);
+        if (EPI == EPI_STORE) *reinterpret_cast<uint4*>(dst) = ov;
+        else store_stream16(dst, ov);
+    } else {
+        const uint2 ov = make_uint2(o[0], o[1]);
+        if (EPI == EPI_STORE) *reinterpret_cast<uint2*>(dst) = ov;
+        else __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, ov), reinterpret_cast<unsigned long long*>(dst));
+    }
 }
 
 }  // namespace moe

@@ -24,8 +24,6 @@
 namespace moe {
 
 constexpr int kTK = 32;            // k-rows per stage
-constexpr int kTBN = 256;          // tile columns
-constexpr int kTBBytes = kTK * kTBN * 2;   // weight bytes per stage (16 KB)
 
 // 16 bytes per lane from global memory straight into LDS at lds_wave_base + lane*16
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
@@ -40,35 +38,40 @@ __device__ __forceinline__ int a_swizzle(int row) { return (0x78 >> (((row >> 2)
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// NWM waves along the rows x 2 along the columns; each owns WM rows x 128 columns
-template <int WM, int NWM, int NS_> struct TileCfg {
+// NWM waves along the rows x 2 along the columns; each owns WM rows x WN columns (WN = 128, or 64 for products
+// with so few columns that 256-column tiles would leave CUs without work)
+template <int WM, int NWM, int NS_, int WN> struct TileCfg {
     static constexpr int NWAVES = NWM * 2;
     static constexpr int BM = NWM * WM;
+    static constexpr int TBN = 2 * WN;                         // tile columns
+    static constexpr int B_BYTES = kTK * TBN * 2;              // weight bytes per stage (16 or 8 KB)
     static constexpr int A_BYTES = BM * 64;                    // activation bytes per stage
-    static constexpr int STAGE = A_BYTES + kTBBytes;
+    static constexpr int STAGE = A_BYTES + B_BYTES;
     // 256-row tiles: 4 stages of 32 KB, one work-group of 8 waves per CU.  128-row tiles: 5 stages of 24 KB and one
     // work-group of 4 waves per CU, or 3 stages and at most 256 registers per lane, so that two work-groups share a
     // CU and one multiplies while the other waits at its barrier: much faster for short K (8192 x 1024 x 4096:
     // 92 against 141 us), slightly slower for long K, where the deeper ring counts.
     static constexpr int NS = NS_;
-    static constexpr int WGS_PER_CU = NS_ * (NWM * WM * 64 + kTBBytes) + NWM * WM * 8 <= 80 * 1024 ? 2 : 1;
+    static constexpr int WGS_PER_CU = NS_ * (NWM * WM * 64 + B_BYTES) + NWM * WM * 8 <= 80 * 1024 && NWM == 2 ? 2 : 1;
     static constexpr int NIA = A_BYTES / 1024 / NWAVES;        // activation loads per wave and stage
-    static constexpr int NIB = kTBBytes / 1024 / NWAVES;       // weight loads per wave and stage
+    static constexpr int NIB = B_BYTES / 1024 / NWAVES;        // weight loads per wave and stage
+    static constexpr int RPI = 1024 / (TBN * 2);               // k-rows one weight load (1 KB) covers: 2 or 4
     // Tiles of 256 rows that hold at most 128 valid ones (lightly loaded experts, the last rows of a busy one) need
     // only half of the activation space; the ring is then cut into 6 stages of 24 KB instead of 4 of 32 KB, which
     // keeps 80 KB of weights in flight instead of 48 KB: such tiles are bound by the rate one CU can stream at.
-    static constexpr bool HAS_LIGHT = NWM == 4;
+    static constexpr bool HAS_LIGHT = NWM == 4 && WN == 128;
     static constexpr int L_ROWS = NWAVES * 16;                 // one activation load per wave and stage
     static constexpr int L_A_BYTES = L_ROWS * 64;
-    static constexpr int L_STAGE = L_A_BYTES + kTBBytes;
+    static constexpr int L_STAGE = L_A_BYTES + B_BYTES;
     static constexpr int L_NS = 6;
     static constexpr int RING = HAS_LIGHT && L_NS * L_STAGE > NS * STAGE ? L_NS * L_STAGE : NS * STAGE;
     static constexpr int LDS_BYTES = RING + BM * 8;
 };
 
-template <int WM, int NWM, int NSX, int EPI>
-__global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
-    typedef TileCfg<WM, NWM, NSX> Cfg;
+template <int WM, int NWM, int NSX, int EPI, int WN>
+__global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
+    typedef TileCfg<WM, NWM, NSX, WN> Cfg;
+    constexpr int TBN = Cfg::TBN, NCF = WN / 16;               // column fragments (= columns per lane) of a wave
     constexpr int BM = Cfg::BM, MSUB = WM / 16, NIB = Cfg::NIB, NTHREADS = NWM * 128;
 
     extern __shared__ __attribute__((aligned(16))) char lds[];   // the ring of stages, then BM row indices
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
     const int c = lane & 15, kg = lane >> 4;
     const int wm = w >> 1, wn = w & 1;
 
-    const int n_tiles = (a.N + kTBN - 1) / kTBN;
+    const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const TileId tile = tile_of_block(a, n_tiles, m_tiles, blockIdx.x);
     const int g = tile.g, nt = tile.nt, mt = tile.inner;
@@ -121,12 +124,12 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
         const int kp = (lane & 3) ^ a_swizzle(r);                 // swizzle
         a_src[i] = a.A + (size_t)arow_sh[r] * a.K + kp * 8;
     }
-    // weights: wave w, load i copies k-rows (w*NIB + i)*2, +1; lane L -> row +L/32, 16-byte column piece L%32
-    const int n0 = nt * kTBN;
-    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * NIB * 2 + (lane >> 5)) * a.N +
-                            min(n0 + (lane & 31) * 8, a.N - 8);       // clamped column: loaded, never stored
-    const size_t b_step2 = (size_t)2 * a.N;
-
+    // weights: wave w, load i copies the RPI k-rows (w*NIB + i)*RPI ..; lane L -> row +L/LPR, 16-byte column piece L%LPR
+    constexpr int RPI = Cfg::RPI, LPR = 64 / RPI;
+    const int n0 = nt * TBN;
+    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * NIB * RPI + lane / LPR) * a.N +
+                            min(n0 + (lane % LPR) * 8, a.N - 8);      // clamped column: loaded, never stored
+    const size_t b_step2 = (size_t)RPI * a.N;
     const int steps = a.K / kTK;
     auto issue = [&](int step) {                                // all loads of one stage, this wave's share
         const int st = min(step, steps - 1);                    // past the end: harmless re-read, keeps the count uniform
@@ -141,36 +144,51 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
             dma16(bp + i * b_step2, __builtin_amdgcn_readfirstlane(base + A_BYTES + (w * NIB + i) * 1024));
     };
 
-    f32x4_t acc[NA][8];
+    f32x4_t acc[NA][NCF];
 #pragma unroll
     for (int i = 0; i < NA; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NCF; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ a_swizzle(R);
     // a_swizzle(R) == a_swizzle(c) because the other terms are multiples of 16
     const int a_lane = (wm * WM + c) * 64 + ((kg ^ a_swizzle(c)) * 16);
-    const int b_lane = A_BYTES + (kg * 8) * (kTBN * 2) + (wn * 128 + c * 8) * 2;
+    const int b_lane = A_BYTES + (kg * 8) * (TBN * 2) + (wn * WN + c * NCF) * 2;
 
-    // operand fragments of one stage in registers
+    // operand fragments of one stage in registers: per k-row the lane's NCF columns (16 or 8 bytes), and the
+    // activation fragments
+    typedef typename std::conditional<NCF == 8, uint4, uint2>::type BRaw;
     struct Frags {
-        uint4 braw[8];
+        BRaw braw[8];
         bf16x8_t af[NA];
     };
     auto read_frags = [&](Frags& f, int buf) {
         if (ACT == 0) return;
         const char* base = lds + buf * STAGE;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const uint4*>(base + b_lane + j * (kTBN * 2));
+        for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const BRaw*>(base + b_lane + j * (TBN * 2));
 #pragma unroll
         for (int ms = 0; ms < ACT; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
+    };
+    // dword q of a lane's row piece
+    auto raw_dw = [](const BRaw& v, int q) -> uint32_t {
+        if constexpr (NCF == 8) return dw(v, q);
+        else return q == 0 ? v.x : v.y;
     };
     auto mma = [&](const Frags& f) {
         if (ACT == 0) return;
 #pragma unroll
-        for (int qq = 0; qq < 4; ++qq) {
-            bf16x8_t blo, bhi;
-            b_frag_pair(f.braw, qq, blo, bhi);
+        for (int qq = 0; qq < NCF / 2; ++qq) {
+            // 8 k-rows x 2 columns of 16-bit values -> two fragments (v_perm_b32), as in the streaming kernel
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t r0 = raw_dw(f.braw[2 * p], qq), r1 = raw_dw(f.braw[2 * p + 1], qq);
+                lo[p] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);   // column 2qq   : k = 2p, 2p+1
+                hi[p] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // column 2qq+1
+            }
+            const bf16x8_t blo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+            const bf16x8_t bhi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
 #pragma unroll
             for (int ms = 0; ms < ACT; ++ms) {
                 acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
@@ -207,23 +225,37 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
     wait_vmcnt<0>();                      // drain the over-issued tail loads before LDS is released
 
     // ---- epilogue ------------------------------------------------------------------------------
-    const int n_lane = n0 + wn * 128 + c * 8;
+    const int n_lane = n0 + wn * WN + c * NCF;
     if (ACT == 0 || n_lane >= a.N) return;
-    float bias[8];
-    load_bias8(a, g, n_lane, bias);
+    float bias[NCF];
+    {
+        float b8[8];
+        if (NCF == 8) load_bias8(a, g, n_lane, b8);
+        else {                                                   // 4 columns: 8 bytes of bias
+#pragma unroll
+            for (int i = 0; i < 8; ++i) b8[i] = 0.f;
+            if (a.bias) {
+                const uint2 bv = *reinterpret_cast<const uint2*>(a.bias + (size_t)g * a.N + n_lane);
+                b8[0] = __uint_as_float(bv.x << 16); b8[1] = __uint_as_float(bv.x & 0xffff0000u);
+                b8[2] = __uint_as_float(bv.y << 16); b8[3] = __uint_as_float(bv.y & 0xffff0000u);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NCF; ++i) bias[i] = b8[i];
+    }
 #pragma unroll
     for (int ms = 0; ms < ACT; ++ms) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int rl = wm * WM + ms * 16 + kg * 4 + r;       // D: rows 4*(lane/16)+r, column lane%16
             if (rl >= nrows) continue;
-            float v[8];
+            float v[NCF];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = acc[ms][i][r] + bias[i];
+            for (int i = 0; i < NCF; ++i) v[i] = acc[ms][i][r] + bias[i];
             int t = 0;
             float gw = 1.f;
             if (EPI == EPI_SCATTER) scatter_lookup(a, g, m0 + rl, t, gw);
-            finish_row<EPI>(a, g, m0 + rl, 0, n_lane, v, t, gw);
+            finish_row<EPI, NCF>(a, g, m0 + rl, 0, n_lane, v, t, gw);
         }
         __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
     }
@@ -243,37 +275,45 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX>::WGS_PER_CU)) voi
     }
 }
 
-template <int WM, int NWM, int NSX, int EPI>
+template <int WM, int NWM, int NSX, int EPI, int WN>
 static int launch_t(const WsGemmArgs& a, hipStream_t s) {
-    constexpr int BM = NWM * WM;
-    const int n_tiles = (a.N + kTBN - 1) / kTBN;
+    constexpr int BM = NWM * WM, TBN = 2 * WN;
+    const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
-    const size_t smem = TileCfg<WM, NWM, NSX>::LDS_BYTES;
+    const size_t smem = TileCfg<WM, NWM, NSX, WN>::LDS_BYTES;
     static bool attr_set = false;            // one flag per instantiation
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, NSX, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, NSX, EPI, WN>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
+    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI, WN>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-template <int EPI>
-static int launch_t_epi(const WsGemmArgs& a, int WM, hipStream_t s) {
-    // 128 x 256 tiles: 2 x 2 waves; 256 x 256 tiles: 4 x 2 waves (64 rows per wave keep the accumulators at 128
-    // registers, which the compiler updates in place; 128 rows per wave fill the file and cost copies)
-    if (WM != 64) return launch_t<64, 4, 4, EPI>(a, s);
-    return a.K <= 2048 ? launch_t<64, 2, 3, EPI>(a, s) : launch_t<64, 2, 5, EPI>(a, s);
+// Tile shapes.  256 x 256 (4 x 2 waves of 64 x 128: the accumulators take 128 registers, which the compiler updates
+// in place; 128 rows per wave fill the file and cost copies) wherever that gives every CU a tile.  Products with few
+// columns (N = d_model in GEMM-2) get 256 x 128 tiles of 4 x 2 waves of 64 x 64 instead: as many tiles, but eight waves
+// per CU rather than the four of a 128 x 256 tile, which is what hides the LDS and barrier latencies.  Groups of at
+// most 128 rows: 128 x 256 (2 x 2 waves), ring depth by K.
+enum TileShape { TILE_128x256, TILE_256x256, TILE_256x128 };
+static TileShape pick_tile(int max_rows, int G, int N) {
+    if (max_rows <= 128) return TILE_128x256;
+    const long long row_tiles = (long long)G * ((max_rows + 255) / 256);
+    if (row_tiles * ((N + 255) / 256) >= 256) return TILE_256x256;
+    if (row_tiles * ((N + 127) / 128) >= 256) return TILE_256x128;
+    return TILE_128x256;
 }
 
-// 128 rows per wave (256 x 256 tiles) when that still gives every CU a tile, else 64 (128 x 256)
-int tgemm_wave_rows(int max_rows, int G, int N) {
-    if (max_rows <= 128) return 64;
-    const long long tiles = (long long)G * ((max_rows + 255) / 256) * ((N + kTBN - 1) / kTBN);
-    return tiles >= 256 ? 128 : 64;
+template <int EPI>
+static int launch_t_epi(const WsGemmArgs& a, hipStream_t s) {
+    switch (pick_tile(a.max_rows, a.G, a.N)) {
+        case TILE_256x256: return launch_t<64, 4, 4, EPI, 128>(a, s);
+        case TILE_256x128: return launch_t<64, 4, 5, EPI, 64>(a, s);
+        default: return a.K <= 2048 ? launch_t<64, 2, 3, EPI, 128>(a, s) : launch_t<64, 2, 5, EPI, 128>(a, s);
+    }
 }
 
 bool tgemm_supported(int K, int N) { return K % kTK == 0 && K >= kTK && N % 8 == 0 && N >= 8; }
@@ -281,12 +321,11 @@ bool tgemm_supported(int K, int N) { return K % kTK == 0 && K >= kTK && N % 8 ==
 int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s) {
     if (a.G <= 0 || a.max_rows <= 0) return MOE_OK;
     if (a.ksplit != 1 || !tgemm_supported(a.K, a.N)) return MOE_ERR_INVALID_ARG;
-    const int WM = tgemm_wave_rows(a.max_rows, a.G, a.N);
     switch (epi) {
-        case EPI_STORE: return launch_t_epi<EPI_STORE>(a, WM, s);
-        case EPI_GELU: return launch_t_epi<EPI_GELU>(a, WM, s);
-        case EPI_SCATTER: return launch_t_epi<EPI_SCATTER>(a, WM, s);
-        case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, WM, s);
+        case EPI_STORE: return launch_t_epi<EPI_STORE>(a, s);
+        case EPI_GELU: return launch_t_epi<EPI_GELU>(a, s);
+        case EPI_SCATTER: return launch_t_epi<EPI_SCATTER>(a, s);
+        case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, s);
         default: return MOE_ERR_INVALID_ARG;
     }
 }
