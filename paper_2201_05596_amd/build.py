@@ -14,6 +14,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
 SOURCES = ["api.hip", "gate.hip", "gate_bf16.hip", "layout.hip", "gemm_simple.hip", "ffn_mfma.hip", "ffn_tile.hip"]
+# stand-alone measurement programs (source with a main()) -> executables beside the library
+PROGRAMS = {"mfma_rate.hip": os.path.join(HERE, "mfma_rate")}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -45,6 +47,10 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    for src, exe in PROGRAMS.items():
+        r = subprocess.run([HIPCC, *FLAGS, os.path.join(CSRC, src), "-o", exe], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
     return LIB

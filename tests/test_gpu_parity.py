@@ -162,7 +162,9 @@ def test_dispatch_exact_and_combine(dtype, T, d, E, k, C):
 @pytest.mark.parametrize("dtype,d,f,E,C,bias", [("f32", 64, 256, 8, 32, True), ("bf16", 256, 1024, 6, 70, True),
                                                 ("bf16", 1024, 4096, 4, 64, False), ("bf16", 2048, 8192, 6, 1, True),
                                                 ("bf16", 264, 520, 3, 130, True), ("bf16", 288, 544, 9, 300, True),
-                                                ("bf16", 512, 96, 8, 100, False)])
+                                                ("bf16", 512, 96, 8, 100, False),
+                                                # many groups, few output columns in the second product: 256 x 128 tiles
+                                                ("bf16", 1024, 128, 32, 200, True), ("bf16", 1000, 160, 33, 250, True)])
 def test_expert_ffn(dtype, d, f, E, C, bias):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
