@@ -82,11 +82,11 @@ struct FfnPlan {
 };
 
 // developer tuning knobs (environment, read once), 0 = not set
-enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_UNFUSEDGATE, KN_COUNT };
+enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_UNFUSEDGATE, KN_SPREAD, KN_COUNT };
 int tune(Knob k) {
     static const char* const names[KN_COUNT] = {"MOE_TUNE_NBUF", "MOE_TUNE_MT", "MOE_TUNE_NW1", "MOE_TUNE_NW2",
                                                 "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE", "MOE_TUNE_F32GATE",
-                                                "MOE_TUNE_UNFUSEDGATE"};
+                                                "MOE_TUNE_UNFUSEDGATE", "MOE_TUNE_SPREAD"};
     static int values[KN_COUNT];
     static bool read = false;
     if (!read) {
@@ -150,7 +150,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.slot_idx = take(T * k * 4);
     L.gate_w = take(T * k * 4);
     L.rows = take(E * 4);
-    L.order = take(E * 4);
+    L.order = take((E + 1) * 4);      // launch order of the experts + the tile-dealing flag
     L.slot_token = take(E * C * 4);
     L.xe = take(plan.mfma ? 0 : E * C * d * es);       // the MFMA path gathers rows inside GEMM-1
     L.h = take(E * C * f * es);
@@ -234,6 +234,7 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
+    a.spread = tune(KN_SPREAD);
     prof_pre(ST_GEMM1, st);
     const int rc = p.tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
     prof_mark(ST_GEMM1, st);
@@ -251,6 +252,7 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
+    a.spread = tune(KN_SPREAD);
     prof_pre(ST_GEMM2, st);
     if (p.ksplit2 == 1) {
         const int epi = scatter ? EPI_SCATTER : EPI_STORE;

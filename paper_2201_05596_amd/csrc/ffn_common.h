@@ -71,7 +71,33 @@ __device__ __forceinline__ TileId tile_of_block(const WsGemmArgs& a, int n_tiles
     }
     return t;
 }
+// Second mapping, for the tiled kernel with many groups of very different sizes (config 5: a few experts at capacity,
+// many with a handful of rows): every XCD takes 1/8 of the column tiles of EVERY group and walks the groups in launch
+// order, row tiles innermost.  All XCDs then carry the same work whatever the row counts are; a weight column tile
+// still enters exactly one L2 (its row tiles run back to back there); only the groups' activation rows are read by
+// all eight.  Because the launch order alternates busy and light groups, the CUs of an XCD run matrix-bound and
+// weight-streaming tiles at the same time, instead of one phase after the other.
+// Which mapping applies is decided on the device, by the flag behind the launch order (only the device knows the row
+// counts); the host sizes the grid for either.
+__host__ __device__ __forceinline__ bool tile_spread_possible(const WsGemmArgs& a, int n_tiles) {
+    return a.order != nullptr && a.spread != 2 && a.ksplit == 1 && a.G >= kXcd && n_tiles % kXcd == 0;
+}
+__device__ __forceinline__ bool tile_spread(const WsGemmArgs& a, int n_tiles) {
+    return tile_spread_possible(a, n_tiles) && (a.spread == 1 || a.order[a.G] != 0);
+}
+__device__ __forceinline__ TileId tile_of_block_spread(const WsGemmArgs& a, int n_tiles, int inner_n, int block) {
+    TileId t;
+    const int xcd = block % kXcd, q = block / kXcd;
+    const int per_x = n_tiles / kXcd, per_group = per_x * inner_n;
+    const int slot = q / per_group, rem = q % per_group;
+    t.nt = xcd * per_x + rem / inner_n;
+    t.inner = rem % inner_n;
+    t.live = slot < a.G;
+    t.g = t.live ? (a.order ? a.order[slot] : slot) : 0;
+    return t;
+}
 inline long long tile_grid_blocks(const WsGemmArgs& a, int n_tiles, int inner_n) {
+    // (the spread mapping needs G * n_tiles * inner_n blocks, never more than the first case below)
     if (a.G >= kXcd) return (long long)(a.G + kXcd - 1) / kXcd * kXcd * n_tiles * inner_n;
     if (a.ksplit == 1 && inner_n >= kXcd) return (long long)a.G * ((inner_n + kXcd - 1) / kXcd) * n_tiles * kXcd;
     return ((long long)a.G * n_tiles + kXcd - 1) / kXcd * kXcd * inner_n;

@@ -84,7 +84,8 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
 
     const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
-    const TileId tile = tile_of_block(a, n_tiles, m_tiles, blockIdx.x);
+    const TileId tile = tile_spread(a, n_tiles) ? tile_of_block_spread(a, n_tiles, m_tiles, blockIdx.x)
+                                                : tile_of_block(a, n_tiles, m_tiles, blockIdx.x);
     const int g = tile.g, nt = tile.nt, mt = tile.inner;
 
     if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NTHREADS);

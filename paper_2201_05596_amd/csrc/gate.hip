@@ -367,10 +367,13 @@ __global__ __launch_bounds__(kRouteTokens) void route_local_kernel(const float* 
 // x) takes the next busiest remaining expert when j + x is even, the next lightest when odd.  All
 // XCDs get the same number of active experts, and while half of them multiply the others stream
 // weights.  Experts without rows follow at the end.  O(E^2) compares, E <= 1024.
-// `sorted` is LDS scratch of E + 1 ints; every thread of the block must call.
+// order[E] (one entry past the list) tells the tiled GEMM how to deal its tiles to the XCDs: 1 when the active
+// experts are of very different sizes (at least a quarter of them hold at most a quarter of the largest one's
+// rows), so that dealing whole experts would leave the XCDs with unequal work; 0 otherwise.
+// `sorted` is LDS scratch of E + 2 ints; every thread of the block must call.
 __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */, int E, int32_t* __restrict__ order,
                                                    int32_t* sorted /* LDS */, int tid, int nthreads) {
-    if (tid == 0) sorted[E] = 0;
+    if (tid == 0) sorted[E] = sorted[E + 1] = 0;
     __syncthreads();
     int active = 0;
     for (int e = tid; e < E; e += nthreads) {
@@ -386,6 +389,14 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
     if (active) atomicAdd(&sorted[E], active);          // integer count in LDS: order-independent
     __syncthreads();
     const int na = sorted[E];
+    {
+        const int largest = rows[sorted[0]];
+        int small = 0;
+        for (int e = tid; e < E; e += nthreads) small += rows[e] > 0 && rows[e] * 4 <= largest ? 1 : 0;
+        if (small) atomicAdd(&sorted[E + 1], small);
+        __syncthreads();
+        if (tid == 0) order[E] = sorted[E + 1] * 4 >= na && na > 0 ? 1 : 0;
+    }
     for (int p = tid; p < E; p += nthreads) {
         int e;
         if (p >= na) {
@@ -403,14 +414,14 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
 
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ expert_rows, int E, int C,
                                                            int32_t* __restrict__ order) {
-    extern __shared__ int32_t smem[];                 // rows [E], sorted [E + 1]
+    extern __shared__ int32_t smem[];                 // rows [E], sorted [E + 2]
     for (int e = threadIdx.x; e < E; e += 256) smem[e] = min(expert_rows[e], C);
     __syncthreads();
     write_expert_order(smem, E, order, smem + E, threadIdx.x, 256);
 }
 
 int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s) {
-    hipLaunchKernelGGL(expert_order_kernel, dim3(1), dim3(256), sizeof(int32_t) * (2 * E + 1), s, expert_rows, E, C, order);
+    hipLaunchKernelGGL(expert_order_kernel, dim3(1), dim3(256), sizeof(int32_t) * (2 * E + 2), s, expert_rows, E, C, order);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -555,7 +566,7 @@ size_t route_finalize_lds_bytes(int E, int k, int TB) {
     const int ncol = k * E;
     const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
     size_t ints = (size_t)(kRouteTokens / TB) * ncol + E + 2 * (size_t)R * ncol;
-    if (ints < (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 1) ints = (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 1;
+    if (ints < (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 2) ints = (size_t)(kRouteTokens / TB) * ncol + 2 * (size_t)E + 2;
     return ints * sizeof(int32_t);
 }
 

@@ -134,7 +134,7 @@ struct WsGemmArgs {
     const uint16_t* B;         // [G, K, N]
     const uint16_t* bias;      // [G, N] or nullptr
     const int32_t* rows;       // [G] device row counts or nullptr -> fixed_rows
-    const int32_t* order;      // [G] groups in launch order (busiest first) or nullptr -> identity
+    const int32_t* order;      // [G + 1] groups in launch order (busiest first), then the tile-dealing flag; or nullptr -> identity
     const int32_t* row_map;    // [G, map_stride]: A-row of (g, r), or nullptr -> g*a_group_stride + r
     int32_t fixed_rows, max_rows, map_stride;
     int32_t G, K, N;
@@ -142,6 +142,7 @@ struct WsGemmArgs {
     uint16_t* out;             // leading dimension N
     long long o_group_stride;
     int32_t ksplit;            // >= 1; > 1 only with EPI_PARTIAL
+    int32_t spread;            // tiled kernel, developer override of the tile dealing: 0 = as order[G] says, 1 = always spread, 2 = never
     float* partial;            // [ksplit, partial_rows, N]
     long long partial_rows;
     // EPI_SCATTER
