@@ -166,6 +166,17 @@ def test_dispatch_exact_and_combine(dtype, T, d, E, k, C):
                                                 # many groups, few output columns in the second product: 256 x 128 tiles
                                                 ("bf16", 1024, 128, 32, 200, True), ("bf16", 1000, 160, 33, 250, True)])
 def test_expert_ffn(dtype, d, f, E, C, bias):
+    _check_expert_ffn(dtype, d, f, E, C, bias, None)
+
+
+def test_expert_ffn_unequal_experts():
+    """Two full experts among nearly empty ones (and a group count that is not a multiple of 8): the tiled kernel
+    deals the column tiles of every expert over the XCDs instead of whole experts."""
+    _check_expert_ffn("bf16", 256, 2048, 9, 300, True, [300, 3, 2, 1, 280, 5, 0, 2, 1])
+    _check_expert_ffn("bf16", 128, 4096, 16, 200, False, [200, 1, 1, 0, 2, 1, 150, 1, 3, 1, 0, 1, 2, 1, 1, 70])
+
+
+def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     g = torch.Generator(device=DEV).manual_seed(d + f)
@@ -173,6 +184,8 @@ def test_expert_ffn(dtype, d, f, E, C, bias):
     rows[0] = C
     if E > 2:
         rows[1] = 0
+    if fixed_rows is not None:
+        rows = torch.tensor(fixed_rows, dtype=torch.int32, device=DEV)
     xe = torch.randn((E, C, d), generator=g, device=DEV).to(tdt)
     W1 = (0.02 * torch.randn((E, d, f), generator=g, device=DEV)).to(tdt)
     W2 = (0.02 * torch.randn((E, f, d), generator=g, device=DEV)).to(tdt)
