@@ -108,17 +108,18 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     // the accumulators of each copy in place in the register file.
     // A wave without valid rows (ACT = 0) still takes part in the loads and barriers, nothing else.
     const int nsub = __builtin_amdgcn_readfirstlane(max(0, (min(nrows - wm * WM, WM) + 15) / 16));
-    auto run = [&](auto act_c, auto light_c) {
+    auto run = [&](auto act_c, auto light_c, auto loada_c) {
     constexpr int ACT = decltype(act_c)::value;
     constexpr bool LIGHT = decltype(light_c)::value;
+    constexpr bool LOADA = decltype(loada_c)::value;           // false: the 16 rows this wave would load do not exist
     constexpr int NA = ACT > 0 ? ACT : 1;                       // array extents
     constexpr int NS = LIGHT ? Cfg::L_NS : Cfg::NS, STAGE = LIGHT ? Cfg::L_STAGE : Cfg::STAGE;
-    constexpr int A_BYTES = LIGHT ? Cfg::L_A_BYTES : Cfg::A_BYTES, NIA = LIGHT ? 1 : Cfg::NIA;
+    constexpr int A_BYTES = LIGHT ? Cfg::L_A_BYTES : Cfg::A_BYTES, NIA = !LOADA ? 0 : LIGHT ? 1 : Cfg::NIA;
     constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
 
     // ---- per-lane sources of the direct loads (fixed for the whole k-loop) ---------------------------
     // activations: wave w, load i copies rows (w*NIA + i)*16 .. +15; lane L -> row +L/4, slot L%4
-    const uint16_t* a_src[NIA];
+    const uint16_t* a_src[NIA > 0 ? NIA : 1];
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
         const int r = (w * NIA + i) * 16 + (lane >> 2);
@@ -261,18 +262,31 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
         __builtin_amdgcn_sched_barrier(0);      // keep the accumulators' live ranges short
     }
     };
-    typedef std::integral_constant<bool, false> Full;
-    typedef std::integral_constant<bool, Cfg::HAS_LIGHT> Light;
-    if (Cfg::HAS_LIGHT && nrows <= Cfg::L_ROWS) {               // uniform over the work-group
-        if (nsub > 2) run(std::integral_constant<int, MSUB>(), Light());
-        else if (nsub == 2) run(std::integral_constant<int, 2>(), Light());
-        else if (nsub == 1) run(std::integral_constant<int, 1>(), Light());
-        else run(std::integral_constant<int, 0>(), Light());
-    } else {
-        if (nsub > 2) run(std::integral_constant<int, MSUB>(), Full());
-        else if (nsub == 2) run(std::integral_constant<int, 2>(), Full());
-        else if (nsub == 1) run(std::integral_constant<int, 1>(), Full());
-        else run(std::integral_constant<int, 0>(), Full());
+    typedef std::integral_constant<bool, false> No;
+    typedef std::integral_constant<bool, true> Yes;
+    bool done = false;
+    if constexpr (Cfg::HAS_LIGHT) {
+        if (nrows <= Cfg::L_ROWS) {                             // uniform over the work-group
+            done = true;
+            // a tile of a nearly empty expert is pure streaming: waves whose 16 activation rows lie past the last
+            // valid row do not load them (the copies would only repeat the last row and take a third of the load slots)
+            if (__builtin_amdgcn_readfirstlane(w * 16 < nrows) || nsub > 2) {
+                if (nsub > 2) run(std::integral_constant<int, MSUB>(), Yes(), Yes());
+                else if (nsub == 2) run(std::integral_constant<int, 2>(), Yes(), Yes());
+                else if (nsub == 1) run(std::integral_constant<int, 1>(), Yes(), Yes());
+                else run(std::integral_constant<int, 0>(), Yes(), Yes());
+            } else {
+                if (nsub == 2) run(std::integral_constant<int, 2>(), Yes(), No());
+                else if (nsub == 1) run(std::integral_constant<int, 1>(), Yes(), No());
+                else run(std::integral_constant<int, 0>(), Yes(), No());
+            }
+        }
+    }
+    if (!done) {
+        if (nsub > 2) run(std::integral_constant<int, MSUB>(), No(), Yes());
+        else if (nsub == 2) run(std::integral_constant<int, 2>(), No(), Yes());
+        else if (nsub == 1) run(std::integral_constant<int, 1>(), No(), Yes());
+        else run(std::integral_constant<int, 0>(), No(), Yes());
     }
 }
 
