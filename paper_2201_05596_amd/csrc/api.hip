@@ -103,7 +103,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
     FfnPlan p{};
     p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
     p.ksplit2 = 1;
-    p.NBUF = tune(KN_NBUF) ? tune(KN_NBUF) : 4;
+    p.NBUF = tune(KN_NBUF) ? tune(KN_NBUF) : 2;
     if (!p.mfma) return p;
     p.tiled = s->capacity > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
               !tune(KN_NOTILE);
