@@ -239,10 +239,15 @@ int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* b
 //            the block is parked in slot_idx until kernel 2 adds the block's base.
 // scratch layout: hist[block][choice][E]
 // ------------------------------------------------------------------------------------------
-template <int K, int NV>
+// SINGLE (at most 256 tokens, one block): the block's totals stay in LDS (tot_sh [K][E]) and the ranks in registers
+// (my_e, my_slot: expert and rank within the expert's choice-j tokens of this thread's token), nothing is parked
+// in global memory.
+template <int K, int NV, bool SINGLE = false>
 __device__ __forceinline__ void route_local_body(int32_t* smem, const float* __restrict__ logits, int T, int E,
                                                  int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot_idx,
-                                                 float* __restrict__ gate_w, int32_t* __restrict__ hist) {
+                                                 float* __restrict__ gate_w, int32_t* __restrict__ hist,
+                                                 int32_t* tot_sh = nullptr, int* my_e_out = nullptr,
+                                                 int* my_slot_out = nullptr) {
     constexpr int NW = kRouteTokens / kWave;
     int32_t* e_sh = smem;                          // [K][256] chosen expert per token of the block
     int32_t* whist = smem + K * kRouteTokens;      // [NW][K][E]
@@ -332,14 +337,20 @@ __device__ __forceinline__ void route_local_body(int32_t* smem, const float* __r
             whist[(ww * K + j) * E + e] = run;
             run += c;
         }
-        hist[((size_t)blockIdx.x * K + j) * E + e] = run;
+        if (SINGLE) tot_sh[j * E + e] = run;
+        else hist[((size_t)blockIdx.x * K + j) * E + e] = run;
     }
     __syncthreads();
     const int t = tb + tid;
-    if (t < T) {
 #pragma unroll
-        for (int j = 0; j < K; ++j)
-            slot_idx[(size_t)t * K + j] = my_rank[j] + whist[(w * K + j) * E + my_e[j]];
+    for (int j = 0; j < K; ++j) {
+        const int slot = t < T ? my_rank[j] + whist[(w * K + j) * E + my_e[j]] : 0;
+        if (SINGLE) {
+            my_e_out[j] = my_e[j];
+            my_slot_out[j] = slot;
+        } else if (t < T) {
+            slot_idx[(size_t)t * K + j] = slot;
+        }
     }
 }
 
@@ -542,9 +553,8 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
                            coarse);
 }
 
-// At most 256 tokens: one block, whose local ranks are already global ones -- both routing kernels in one
-// launch.  What the first half wrote to global memory (chosen experts, ranks, the histogram) is read back by
-// other threads of the same block after the barrier.
+// At most 256 tokens (decode): one block, whose local ranks are already global ones -- the whole routing in one
+// launch with a single memory round trip (the logits): totals and ranks stay in LDS and registers.
 template <int K, int NV>
 __global__ __launch_bounds__(kRouteTokens) void route_single_kernel(const float* __restrict__ logits, int T, int E, int C,
                                                                     int32_t* __restrict__ expert_idx,
@@ -555,11 +565,31 @@ __global__ __launch_bounds__(kRouteTokens) void route_single_kernel(const float*
                                                                     int32_t* __restrict__ expert_order,
                                                                     int32_t* __restrict__ hist) {
     extern __shared__ int32_t smem[];
-    route_local_body<K, NV>(smem, logits, T, E, expert_idx, slot_idx, gate_w, hist);
-    __threadfence_block();
+    constexpr int NW = kRouteTokens / kWave;
+    int32_t* tot_sh = smem + K * kRouteTokens + NW * K * E;     // [K][E] tokens per (choice, expert)
+    int32_t* rows_sh = tot_sh + K * E;                          // [E]
+    int32_t* sorted = rows_sh + E;                              // [E + 2]
+    const int tid = threadIdx.x;
+    int my_e[K], my_slot[K];
+    route_local_body<K, NV, true>(smem, logits, T, E, expert_idx, slot_idx, gate_w, hist, tot_sh, my_e, my_slot);
+    for (int e = tid; e < E; e += kRouteTokens) {
+        const int rows = min(tot_sh[e] + (K == 2 ? tot_sh[E + e] : 0), C);
+        rows_sh[e] = rows;
+        expert_rows[e] = rows;
+    }
+    if (tid < T) {
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const int e = my_e[j];
+            const int loc = my_slot[j] + (j == 1 ? tot_sh[e] : 0);   // second choices rank behind all first ones
+            if (loc < C) slot_token[(size_t)e * C + loc] = tid;
+            slot_idx[(size_t)tid * K + j] = loc < C ? loc : -1;
+        }
+    }
     __syncthreads();
-    route_finalize_body<K>(smem, T, E, C, 1, kRouteTokens, expert_idx, slot_idx, expert_rows, slot_token, expert_order, hist,
-                           hist);
+    for (long long i = tid; i < (long long)E * C; i += kRouteTokens)
+        if ((int)(i % C) >= rows_sh[i / C]) slot_token[i] = -1;
+    if (expert_order) write_expert_order(rows_sh, E, expert_order, sorted, tid, kRouteTokens);
 }
 
 size_t route_finalize_lds_bytes(int E, int k, int TB) {
@@ -597,8 +627,7 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
     const int NW = kRouteTokens / kWave;
     const size_t sm1 = sizeof(int32_t) * ((size_t)k * kRouteTokens + (size_t)NW * k * E);
     if (nb == 1) {
-        const size_t sm2 = route_finalize_lds_bytes(E, k, kRouteTokens);
-        const size_t sm = sm1 > sm2 ? sm1 : sm2;
+        const size_t sm = sm1 + sizeof(int32_t) * ((size_t)k * E + 2 * (size_t)E + 2);   // + totals, rows, order scratch
 #define MOE_ROUTE_SINGLE(K, NV)                                                                                      \
     hipLaunchKernelGGL((route_single_kernel<K, NV>), dim3(1), dim3(kRouteTokens), sm, s, logits, T, E, C, expert_idx, \
                        slot_idx, gate_w, expert_rows, slot_token, expert_order, scratch)
