@@ -109,18 +109,6 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
 
     const int g = cur.g, m0 = cur.m0, nrows = cur.nrows, ch_beg = cur.ch_beg, ch_end = cur.ch_end;
 
-    // ---- A rows of the tile ----------------------------------------------------------
-    lds_barrier();                                              // the previous tile's readers are done
-    if (tid < MT) {
-        const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
-        long long ar;
-        if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
-        else ar = (long long)g * a.a_group_stride + r;
-        arow_sh[tid] = ar;
-        if (EPI == EPI_SCATTER) scatter_lookup(a, g, r, tok_sh[tid], gw_sh[tid]);
-    }
-    lds_barrier();
-
     // ---- per-lane weight pointers: 8 columns n_lane..n_lane+7 of rows k, this tile and the next ----
     const int n_lane_raw = lane_col(cur.nt);
     const bool col_ok = n_lane_raw < a.N;
@@ -132,6 +120,38 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
     const uint16_t* Bn = a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
     const int k_end_pad = ch_end * KC;                          // first k that belongs to the next tile
     const int k_next = has_next ? nxt.ch_beg * KC : 0;
+
+    // weight super-fragment: rows k0 + kg*8 + j, j = 0..7.  K is a multiple of 8: a lane's 8 rows are all
+    // inside or all outside.  Rows in [K, k_end_pad) re-read the last 8 rows (in bounds) and meet zeros on
+    // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
+    // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
+    // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
+    auto b_load = [&](uint4 (&dst)[8], int k0) {
+        const int kk = k0 + kg * 8;
+        const bool own = kk < k_end_pad;
+        const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
+    };
+    // The tile's first weight fragments go out before anything else (unless the previous tile already fetched
+    // them): the row table and the epilogue inputs below cost another memory round trip or two, which the
+    // weights now share instead of following.
+    if (!primed && ch_beg < ch_end) {
+#pragma unroll
+        for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
+    }
+
+    // ---- A rows of the tile ----------------------------------------------------------
+    lds_barrier();                                              // the previous tile's readers are done
+    if (tid < MT) {
+        const int r = m0 + min(tid, nrows - 1);                 // rows past the end alias the last valid one
+        long long ar;
+        if (a.row_map) ar = a.row_map[(size_t)g * a.map_stride + r];
+        else ar = (long long)g * a.a_group_stride + r;
+        arow_sh[tid] = ar;
+        if (EPI == EPI_SCATTER) scatter_lookup(a, g, r, tok_sh[tid], gw_sh[tid]);
+    }
+    lds_barrier();
 
     f32x4_t acc[MSUB][8];
 #pragma unroll
@@ -167,18 +187,6 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
         }
     };
 
-    // weight super-fragment: rows k0 + kg*8 + j, j = 0..7.  K is a multiple of 8: a lane's 8 rows are all
-    // inside or all outside.  Rows in [K, k_end_pad) re-read the last 8 rows (in bounds) and meet zeros on
-    // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
-    // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
-    // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
-    auto b_load = [&](uint4 (&dst)[8], int k0) {
-        const int kk = k0 + kg * 8;
-        const bool own = kk < k_end_pad;
-        const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
-    };
     auto sf_compute = [&](const uint4 (&src)[8], const char* a_lane) {
         bf16x8_t af[MSUB];
 #pragma unroll
@@ -197,12 +205,7 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
     };
 
     if (ch_beg < ch_end) {
-        // prologue: first weight super-fragments in flight (unless the previous tile already
-        // fetched them), first activation chunk in LDS
-        if (!primed) {
-#pragma unroll
-            for (int b = 0; b < NBUF - 1; ++b) b_load(raw[b], ch_beg * KC + b * kSF);
-        }
+        // prologue: first activation chunk in LDS (the first weight super-fragments are in flight already)
         a_load(ch_beg);
         a_store(ch_beg, 0);
         lds_barrier();
