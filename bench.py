@@ -35,10 +35,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by a copy kernel of known size; keyed by workload.  Filled from profiles/*.md.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2", "expert_gemm1"): 1178542080,   # profiles/wsgemm_expert_gemm_c2.md
-    ("c2", "expert_gemm2"): 1179408794,
-    ("c4", "expert_gemm1"): 1637836595,   # profiles/wsgemm_decode_c4.md
-    ("c4", "expert_gemm2"): 1622278144,
+    ("c2", "expert_gemm1"): 1161762918,   # profiles/wsgemm_expert_gemm_c2.md
+    ("c2", "expert_gemm2"): 1162602291,
+    ("c4", "expert_gemm1"): 1627605606,   # profiles/wsgemm_decode_c4.md
+    ("c4", "expert_gemm2"): 1613486490,
 }
 
 

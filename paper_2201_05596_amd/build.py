@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
 SOURCES = ["api.hip", "gate.hip", "gate_bf16.hip", "layout.hip", "gemm_simple.hip", "ffn_mfma.hip", "ffn_tile.hip"]
 # stand-alone measurement programs (source with a main()) -> executables beside the library
-PROGRAMS = {"mfma_rate.hip": os.path.join(HERE, "mfma_rate")}
+PROGRAMS = {"mfma_rate.hip": os.path.join(HERE, "mfma_rate"), "hbm_rate.hip": os.path.join(HERE, "hbm_rate")}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
