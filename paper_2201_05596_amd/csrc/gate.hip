@@ -386,16 +386,34 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
                                                    int32_t* sorted /* LDS */, int tid, int nthreads) {
     if (tid == 0) sorted[E] = sorted[E + 1] = 0;
     __syncthreads();
+    // rank of expert e = number of experts that come before it.  With fewer experts than threads, `parts` adjacent
+    // lanes share an expert, each comparing it with a slice of the others (8 independent LDS reads at a time).
+    int parts = 1;
+    while (parts < 16 && parts * 2 * E <= nthreads) parts *= 2;
+    const int part = tid % parts, slice = (E + parts - 1) / parts;
+    const int lo = part * slice, hi = min(E, lo + slice);
     int active = 0;
-    for (int e = tid; e < E; e += nthreads) {
-        const int r = rows[e];
-        int rank = 0;
-        for (int o = 0; o < E; ++o) {
+    for (int e0 = 0; e0 < E; e0 += nthreads / parts) {          // same trip count for every thread
+        const int e = e0 + tid / parts;
+        const bool ok = e < E;
+        const int r = ok ? rows[e] : 0;
+        int rank = 0, o = lo;
+        for (; o + 8 <= hi; o += 8) {
+            int ro[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ro[i] = rows[o + i];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rank += (ro[i] > r || (ro[i] == r && o + i < e)) ? 1 : 0;
+        }
+        for (; o < hi; ++o) {
             const int ro = rows[o];
             rank += (ro > r || (ro == r && o < e)) ? 1 : 0;
         }
-        sorted[rank] = e;
-        active += r > 0 ? 1 : 0;
+        for (int m = 1; m < parts; m <<= 1) rank += __shfl_xor(rank, m);
+        if (ok && part == 0) {
+            sorted[rank] = e;
+            active += r > 0 ? 1 : 0;
+        }
     }
     if (active) atomicAdd(&sorted[E], active);          // integer count in LDS: order-independent
     __syncthreads();
