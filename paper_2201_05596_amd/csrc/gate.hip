@@ -551,7 +551,10 @@ __device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E,
         const int e = (int)(i / C), c = (int)(i % C);
         if (c >= rows_sh[e]) slot_token[i] = -1;
     }
-    if (b == 0) {
+    // The rows per expert and the launch order are the work of one block: with an order to write, of an extra block
+    // behind the last one (no tokens, no slots: everything above ran empty for it), so that the ranking does not
+    // lengthen a block that also has tokens to place.
+    if (b == (expert_order ? nblocks : 0)) {
         for (int e = tid; e < E; e += kRouteTokens) expert_rows[e] = rows_sh[e];
         if (expert_order) write_expert_order(rows_sh, E, expert_order, part, tid, kRouteTokens);   // part: free by now
     }
@@ -623,11 +626,12 @@ int launch_route_finalize(int T, int E, int k, int C, int TB, const int32_t* exp
                           const int32_t* coarse, hipStream_t s) {
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const size_t sm = route_finalize_lds_bytes(E, k, TB);
+    const int grid = nb + (expert_order ? 1 : 0);               // + the block that ranks the experts
     if (k == 1)
-        hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(nb), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
+        hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(grid), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
                            slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
     else
-        hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(nb), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
+        hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(grid), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
                            slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
