@@ -264,6 +264,15 @@ def test_layer_single_expert_is_dense_ffn():
     assert stats["dropped_tokens"] == 0
 
 
+@pytest.mark.parametrize("top_k", [1, 2])
+def test_layer_no_drop_mode(top_k):
+    """Capacity large enough for every choice of every token (C = T): nothing is dropped, whatever the skew."""
+    cfg = CONFIGS["c5"].scaled(name="nodrop", T=300, E=6, d_model=256, d_ffn=512, top_k=top_k, capacity_factor=6.0 / top_k)
+    assert cfg.capacity == cfg.T
+    stats = U.check_layer(make_inputs(cfg, DEV, bias_std=0.05))
+    assert stats["dropped_tokens"] == 0 and stats["kept"] == cfg.T * top_k
+
+
 def test_layer_deterministic():
     inp = make_inputs(REDUCED["c5r"], DEV)
     a = U.gpu_forward(inp)["out"].clone()
