@@ -2,15 +2,15 @@
 // the dense branch of Residual-MoE (paper Sec. 4.1.1), where the products are bound by the matrix
 // cores, not by weight traffic.
 //
-// A work-group of NWM x 2 waves owns a (NWM*64) x 256 output tile; a wave owns 64 x 128 of it.
-// Both operands pass through LDS in 32-deep k-stages, kNS stages deep, filled by direct
+// A work-group of NWM x 2 waves owns a (NWM*64) x (2*WN) output tile; a wave owns 64 x WN of it (WN = 128, or 64
+// for products with few columns).  Both operands pass through LDS in 32-deep k-stages, 3 to 6 stages deep, filled by direct
 // global->LDS loads (global_load_lds_dwordx4: 16 bytes per lane, a wave writes 1 KB of contiguous
-// LDS per instruction, no staging registers), so kNS-1 stages are always in flight:
-//   * weights: 32 k-rows x 256 columns, K-major exactly as in memory (a wave instruction copies
-//     two 512-byte rows); a wave reads its 128 columns as eight 16-byte row pieces per lane and
-//     turns them into eight MFMA B fragments with the same in-register 8x8 transpose as the
-//     streaming kernel.  Each weight byte is fetched from L2 once per work-group and serves 2*WM rows;
-//   * activations: (2*WM) rows x 64 bytes.  Direct loads leave no room for row padding, so bank
+// LDS per instruction, no staging registers), so all stages but one are always in flight:
+//   * weights: 32 k-rows x 2*WN columns, K-major exactly as in memory (a wave instruction copies
+//     two or four whole rows); a wave reads its WN columns as eight row pieces per lane and turns
+//     them into WN/16 MFMA B fragments with the same in-register transpose as the streaming
+//     kernel.  Each weight byte is fetched from L2 once per work-group and serves NWM*WM rows;
+//   * activations: NWM*WM rows x 64 bytes.  Direct loads leave no room for row padding, so bank
 //     conflicts of the A-fragment reads (16 lanes, 16 rows, same k) are avoided by a swizzle done
 //     on the global side: 16-byte slot `pos` of row r holds k-piece pos ^ a_swizzle(r).
 // The direct loads are issued through inline asm: the compiler then does not know they write LDS
