@@ -129,8 +129,14 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     // weights: wave w, load i copies the RPI k-rows (w*NIB + i)*RPI ..; lane L -> row +L/LPR, 16-byte column piece L%LPR
     constexpr int RPI = Cfg::RPI, LPR = 64 / RPI;
     const int n0 = nt * TBN;
-    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)(w * NIB * RPI + lane / LPR) * a.N +
-                            min(n0 + (lane % LPR) * 8, a.N - 8);      // clamped column: loaded, never stored
+    // With 128-column tiles a k-row is 256 bytes and a lane reads 8 bytes of it, so the two k-groups (rows 8 apart =
+    // 2 KB) that one pass of such an LDS read serves would meet on the same banks: k-rows with bit 3 set are
+    // stored with their two 128-byte halves swapped (b_half_swap), on this side by fetching the other half.
+    static_assert(WN == 128 || NIB == 1, "the half swap assumes one weight load per wave and stage");
+    const int b_row = w * NIB * RPI + lane / LPR;
+    const int b_piece = (lane % LPR) ^ (WN == 64 ? ((b_row >> 3) & 1) * 8 : 0);
+    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)b_row * a.N +
+                            min(n0 + b_piece * 8, a.N - 8);           // clamped column: loaded, never stored
     const size_t b_step2 = (size_t)RPI * a.N;
     const int steps = a.K / kTK;
     auto issue = [&](int step) {                                // all loads of one stage, this wave's share
@@ -155,7 +161,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ a_swizzle(R);
     // a_swizzle(R) == a_swizzle(c) because the other terms are multiples of 16
     const int a_lane = (wm * WM + c) * 64 + ((kg ^ a_swizzle(c)) * 16);
-    const int b_lane = A_BYTES + (kg * 8) * (TBN * 2) + (wn * WN + c * NCF) * 2;
+    const int b_lane = A_BYTES + (kg * 8) * (TBN * 2) + (((wn * WN + c * NCF) * 2) ^ (WN == 64 ? (kg & 1) * 128 : 0));
 
     // operand fragments of one stage in registers: per k-row the lane's NCF columns (16 or 8 bytes), and the
     // activation fragments
