@@ -78,7 +78,8 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     long long* arow_sh = reinterpret_cast<long long*>(lds + Cfg::RING);
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));   // LDS byte offset of the segment
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave number, in a scalar register
     const int c = lane & 15, kg = lane >> 4;
     const int wm = w >> 1, wn = w & 1;
 
