@@ -303,6 +303,7 @@ static int launch_t(const WsGemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
+    if (blocks > (1ll << 30)) return MOE_ERR_UNSUPPORTED;        // block indices are ints in the kernel
     const size_t smem = TileCfg<WM, NWM, NSX, WN>::LDS_BYTES;
     static bool attr_set = false;            // one flag per instantiation
     if (!attr_set) {
