@@ -320,7 +320,9 @@ static int launch_t(const WsGemmArgs& a, hipStream_t s) {
 // in place; 128 rows per wave fill the file and cost copies) wherever that gives every CU a tile.  Products with few
 // columns (N = d_model in GEMM-2) get 256 x 128 tiles of 4 x 2 waves of 64 x 64 instead: as many tiles, but eight waves
 // per CU rather than the four of a 128 x 256 tile, which is what hides the LDS and barrier latencies.  Groups of at
-// most 128 rows: 128 x 256 (2 x 2 waves), ring depth by K.
+// most 128 rows: 128 x 256 tiles; for short K as 2 x 2 waves of 64 x 128, 3 stages, two work-groups per CU; for long K
+// (few, long tiles: one per CU) as 4 x 2 waves of 32 x 128 with 6 stages of 24 KB -- eight waves hide the latencies
+// better than four there (c3b GEMM-2: 113 against 116 us), for short K the two work-groups do (121 against 127 us).
 enum TileShape { TILE_128x256, TILE_256x256, TILE_256x128 };
 static TileShape pick_tile(int max_rows, int G, int N) {
     if (max_rows <= 128) return TILE_128x256;
@@ -335,7 +337,7 @@ static int launch_t_epi(const WsGemmArgs& a, hipStream_t s) {
     switch (pick_tile(a.max_rows, a.G, a.N)) {
         case TILE_256x256: return launch_t<64, 4, 4, EPI, 128>(a, s);
         case TILE_256x128: return launch_t<64, 4, 5, EPI, 64>(a, s);
-        default: return a.K <= 2048 ? launch_t<64, 2, 3, EPI, 128>(a, s) : launch_t<64, 2, 5, EPI, 128>(a, s);
+        default: return a.K <= 2048 ? launch_t<64, 2, 3, EPI, 128>(a, s) : launch_t<32, 4, 5, EPI, 128>(a, s);
     }
 }
 
