@@ -7,7 +7,8 @@
 // non-temporal hint.  "strips": a [G][K][N] array of 2-byte weights; a wave reads a strip of 128 columns
 // (256 bytes per row, 4 rows per load instruction) down all K rows, non-temporal, 8 loads in flight; either
 // waves dealt to the XCDs in launch order, or work-groups of two waves with all strips of a matrix on one XCD
-// (as the GEMM deals its tiles).
+// (as the GEMM deals its tiles), or 256 resident work-groups of four waves that walk their XCD's strips (the
+// occupancy of the 64-row GEMM kernels: one wave per SIMD).
 #include <hip/hip_runtime.h>
 #include <cstdint>
 #include <cstdio>
@@ -72,6 +73,30 @@ __global__ __launch_bounds__(256) void read_strips(const char* __restrict__ p, i
     consume(acc, sink);
 }
 
+// As read_strips<true>, but with the occupancy the MT = 64 GEMM kernels have: one work-group of 4 waves per CU
+// (one wave per SIMD), each wave walking the strips w, w + 1024, ... of its XCD's matrices.
+__global__ __launch_bounds__(256) void read_strips_resident(const char* __restrict__ p, int G, int K, int N, u32x4_t* sink) {
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int xcd = blockIdx.x % 8, per_g = N / 512;                 // work-group tiles of 4 strips per matrix
+    const int groups_per_xcd = (G + 7) / 8;
+    u32x4_t acc = {0, 0, 0, 0};
+    for (int q = blockIdx.x / 8; q < groups_per_xcd * per_g; q += gridDim.x / 8) {
+        const int g = (q / per_g) * 8 + xcd, st = (q % per_g) * 4 + w;
+        if (g >= G) continue;
+        const char* base = p + (size_t)g * K * N * 2 + (size_t)(lane >> 4) * N * 2 + st * 256 + (lane & 15) * 16;
+        for (int k = 0; k + 4 * U <= K; k += 4 * U) {
+            u32x4_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + (size_t)(k + 4 * u) * N * 2));
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc ^= v[u];
+        }
+    }
+    consume(acc, sink);
+}
+
 template <class F> static float best_ms(F launch) {
     hipEvent_t e0, e1;
     (void)hipEventCreate(&e0);
@@ -115,9 +140,10 @@ int main() {
         const int b1 = (int)((waves + 3) / 4), b2 = (s.G + 7) / 8 * 8 * (s.N / 256);
         const float t1 = best_ms([&] { hipLaunchKernelGGL((read_strips<false>), dim3(b1), dim3(256), 0, 0, p, s.G, s.K, s.N, sink); });
         const float t2 = best_ms([&] { hipLaunchKernelGGL((read_strips<true>), dim3(b2), dim3(128), 0, 0, p, s.G, s.K, s.N, sink); });
+        const float t3 = s.N % 512 ? 0.f : best_ms([&] { hipLaunchKernelGGL(read_strips_resident, dim3(256), dim3(256), 0, 0, p, s.G, s.K, s.N, sink); });
         printf("{\"pattern\": \"strips\", \"weights\": \"%s\", \"G\": %d, \"K\": %d, \"N\": %d, \"MiB\": %zu, \"waves\": %zu, "
-               "\"launch_order_TBps\": %.2f, \"matrix_per_xcd_TBps\": %.2f}\n", s.name, s.G, s.K, s.N, total >> 20, waves,
-               total / (t1 * 1e9), total / (t2 * 1e9));
+               "\"launch_order_TBps\": %.2f, \"matrix_per_xcd_TBps\": %.2f, \"one_wave_per_simd_TBps\": %.2f}\n", s.name, s.G, s.K, s.N,
+               total >> 20, waves, total / (t1 * 1e9), total / (t2 * 1e9), t3 > 0.f ? total / (t3 * 1e9) : 0.0);
     }
     CHECK(hipGetLastError());
     return 0;
