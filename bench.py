@@ -42,6 +42,14 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# What a kernel that only reads the same weights in the same access pattern reaches (GB/s), measured with
+# paper_2201_05596_amd/hbm_rate (profiles/hbm_read_ceiling.md): context for roofline.frac, not its denominator.
+MEASURED_READ_CEILING_GBS = {
+    ("c2", "expert_gemm1"): 6850.0,
+    ("c2", "expert_gemm2"): 6910.0,
+}
+
+
 def algorithmic_bytes(cfg, rows):
     """Bytes the method itself has to move, from the actual per-expert row counts."""
     d, f, T = cfg.d_model, cfg.d_ffn, cfg.T
@@ -159,6 +167,10 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
                 "algorithmic_bytes": alg[dom], "avg_ms": dom_ms}
+    ceiling = MEASURED_READ_CEILING_GBS.get((cfg.name, dom))
+    if ceiling:
+        roofline["read_only_kernel_GBps"] = ceiling
+        roofline["frac_of_read_only_kernel"] = achieved / ceiling
     layer_gbs = alg["layer"] / (ms_per_step * 1e-3) / 1e9
     layer_tflops = alg["flops"] / (ms_per_step * 1e-3) / 1e12
 
