@@ -102,6 +102,8 @@ def main() -> int:
     ap.add_argument("--no-stage-events", action="store_true",
                     help="experiment: time the steps without the library's per-stage events (no roofline then)")
     ap.add_argument("--all-stage-events", action="store_true", help="time every stage (more events, slower step)")
+    ap.add_argument("--event-stride", type=int, default=5,
+                    help="stage events are recorded in every n-th timed step only (the first, the (n+1)-th, ...)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -131,9 +133,11 @@ def main() -> int:
     torch.cuda.synchronize()
 
     if not args.no_stage_events:
-        # events only around the two expert GEMMs (the roofline kernel is the longer one): three per step
+        # events only around the two expert GEMMs (the roofline kernel is the longer one): three per timed step, and
+        # only every --event-stride-th step is timed that way (1.5 us per event is 1.5 % of a c2 step)
         moe.moe_profile_select(None if args.all_stage_events else ["expert_gemm1", "expert_gemm2"])
-        moe.moe_profile_enable(args.steps)
+        moe.moe_profile_stride(args.event_stride)
+        moe.moe_profile_enable((args.steps + args.event_stride - 1) // args.event_stride)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):

@@ -151,9 +151,14 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
  * mean fewer events and less disturbance of the call being timed.
  * moe_profile_elapsed(call, ms) waits for that call's last event and fills
  * ms[moe_profile_stage_count()] with the milliseconds per stage (0 for stages
- * the call did not run).  Not thread-safe. */
+ * the call did not run).  moe_profile_stride(n >= 1, default 1) times only every
+ * n-th call after the last moe_profile_enable (the first, the (n+1)-th, ...),
+ * so that a long timed run is disturbed by events in 1/n of its calls only;
+ * "the next n calls" of moe_profile_enable then means the next n timed calls.
+ * Not thread-safe. */
 int moe_profile_enable(int max_calls);
 int moe_profile_select(unsigned stage_mask);
+int moe_profile_stride(int every_nth_call);
 int moe_profile_calls(void);
 int moe_profile_stage_count(void);
 const char* moe_profile_stage_name(int stage);

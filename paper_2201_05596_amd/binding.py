@@ -22,7 +22,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_dispatch",
                 "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
-                "moe_profile_calls",
+                "moe_profile_stride", "moe_profile_calls",
                 "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
 
 
@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_profile_enable.argtypes = [i32]
     lib.moe_profile_select.restype = i32
     lib.moe_profile_select.argtypes = [ctypes.c_uint]
+    lib.moe_profile_stride.restype = i32
+    lib.moe_profile_stride.argtypes = [i32]
     lib.moe_profile_calls.restype = i32
     lib.moe_profile_calls.argtypes = []
     lib.moe_profile_stage_count.restype = i32
@@ -184,6 +186,10 @@ def moe_profile_select(stage_names=None) -> None:
     names = moe_profile_stage_names()
     mask = 0xFFFFFFFF if stage_names is None else sum(1 << names.index(n) for n in stage_names)
     _check("moe_profile_select", load_library().moe_profile_select(mask))
+
+
+def moe_profile_stride(every_nth_call: int) -> None:
+    _check("moe_profile_stride", load_library().moe_profile_stride(int(every_nth_call)))
 
 
 def moe_profile_calls() -> int:

@@ -17,6 +17,7 @@ const char* const kStageNames[ST_COUNT] = {"gate_logits", "gate_route", "dispatc
                                            "splitk_reduce", "dense_gemm1", "dense_gemm2", "combine"};
 struct Profiler {
     int max_calls = 0, calls = 0, cur = -1;
+    int stride = 1, seen = 0;       // only every stride-th call since the last enable is timed
     unsigned mask = ~0u;            // stages that get their own time
     bool dirty = false;             // kernels were launched since the last recorded event
     std::vector<hipEvent_t> ev;     // [max_calls][kMarks]
@@ -36,6 +37,7 @@ void prof_record(int stage, hipStream_t st) {
 void prof_begin(hipStream_t st) {
     g_prof.cur = -1;
     if (g_prof.max_calls == 0 || g_prof.calls >= g_prof.max_calls) return;
+    if (g_prof.seen++ % g_prof.stride != 0) return;
     g_prof.cur = g_prof.calls++;
     g_prof.nmarks[g_prof.cur] = 0;
     g_prof.dirty = true;            // whatever ran before the call
@@ -476,7 +478,7 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
 int moe_profile_enable(int max_calls) {
     for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
     g_prof.ev.clear(); g_prof.stage.clear(); g_prof.nmarks.clear();
-    g_prof.max_calls = 0; g_prof.calls = 0; g_prof.cur = -1;
+    g_prof.max_calls = 0; g_prof.calls = 0; g_prof.cur = -1; g_prof.seen = 0;
     if (max_calls <= 0) return MOE_OK;
     if (max_calls > 4096) return MOE_ERR_INVALID_ARG;
     const size_t n = (size_t)max_calls * kMarks;
@@ -491,6 +493,12 @@ int moe_profile_enable(int max_calls) {
 
 int moe_profile_select(unsigned stage_mask) {
     g_prof.mask = stage_mask;
+    return MOE_OK;
+}
+
+int moe_profile_stride(int every_nth_call) {
+    if (every_nth_call < 1) return MOE_ERR_INVALID_ARG;
+    g_prof.stride = every_nth_call;
     return MOE_OK;
 }
 

@@ -336,6 +336,15 @@ def test_stage_timing_api():
         torch.cuda.synchronize()
         ms = dict(zip(names, m.moe_profile_elapsed(0)))
         assert ms["expert_gemm1"] > 0.0 and ms["expert_gemm2"] == 0.0 and ms["gate_logits"] == 0.0
+        m.moe_profile_enable(0)
+        m.moe_profile_stride(3)                  # calls 0, 3, 6 of the next seven are timed
+        m.moe_profile_enable(5)
+        for _ in range(7):
+            layer(inp.x)
+        torch.cuda.synchronize()
+        assert m.moe_profile_calls() == 3
+        assert dict(zip(names, m.moe_profile_elapsed(2)))["expert_gemm1"] > 0.0
     finally:
         m.moe_profile_enable(0)
         m.moe_profile_select(None)
+        m.moe_profile_stride(1)
