@@ -295,7 +295,7 @@ def test_residual_with_zero_experts_equals_dense_branch():
 
 @pytest.mark.parametrize("name", ["c2", "c3a", "c3b", "c4"])
 def test_layer_full_size(name):
-    """The BASELINE configurations at full size, in the launch configuration bench.py times."""
+    """The benchmark workloads c2, c3a, c3b, c4 at full size, in the launch configuration bench.py times."""
     print(f"case full {name}", flush=True)
     stats = U.check_layer(make_inputs(CONFIGS[name], DEV), lazy_experts=True)
     print(name, stats, flush=True)

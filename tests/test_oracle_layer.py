@@ -128,7 +128,7 @@ def test_dispatch_combine_roundtrip():
 
 
 def test_tiny_config_runs_and_is_self_consistent():
-    # BASELINE config 1 (fp32, T=256, E=8, C=32): the oracle finishes well under a second.
+    # workload c1 (fp32, T=256, E=8, C=32): the oracle finishes well under a second.
     cfg = CONFIGS["c1"]
     inp = make_inputs(cfg, "cpu", bias_std=0.02)
     a = {k: to_f32_numpy(v) for k, v in inp.tensors().items()}
