@@ -1,21 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE-layer forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c5] [--only] [--no-cpu-baseline]
 
 One "step" is one whole moe_layer_forward call (gate -> capacity routing ->
 dispatch -> expert FFNs -> combine [+ dense branch]) over one batch of seeded
 synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
+The headline workload (--config, default c5: the largest single-GPU
+configuration) is timed for exactly K steps after W warm-up steps; the same
+line carries one sub-record per benchmark configuration (c2, c3a, c3b, c4, c5)
+under "configs" unless --only is given.  Before the W warm-up steps every
+workload runs RAMP untimed steps: the matrix-core-bound ones are 5-10 % slower
+while the engine clock is still settling.
+
   value / unit     tokens/s of the whole call (input tokens, dropped ones included)
-  roofline         the dominant kernel (the longer of the two expert GEMMs):
-                   algorithmic bytes per launch / its mean duration, measured with
-                   HIP events recorded by the library on the launch stream inside
-                   the timed region; `traffic` is the rocprofv3 FETCH_SIZE+WRITE_SIZE
-                   figure for the same launch (see profiles/), or null
-  layer_roofline   the same for the whole call against the layer's algorithmic bytes
-  cpu_baseline     the fp64 NumPy oracle on the host cores, one full step of the
-                   same workload (reported baseline, not the target)
+  roofline         which roofline binds the workload (the larger of algorithmic
+                   bytes / 8 TB/s and algorithmic flops / 2.5 PFLOP/s), and the
+                   longest kernel of the call against that roofline: its
+                   algorithmic bytes (weights and biases of the experts it
+                   touches) or flops per launch / its mean duration, from HIP
+                   events the library records on the launch stream inside the
+                   timed region.  `traffic` is the HBM traffic of that kernel
+                   from separate rocprofv3 --pmc runs (see profiles/), or null.
+  layer_roofline   the whole call against the layer's algorithmic bytes and flops
+  cpu_baseline     the fp64 NumPy oracle on the host cores on a bounded sample of
+                   the headline workload (reported baseline, not the target)
 """
 from __future__ import annotations
 
@@ -29,46 +39,117 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+RAMP_STEPS = 100                # untimed steps before the warm-up steps (clock settling)
+EVENT_STRIDE = 5                # stage events are recorded in every 5th timed step only
+SUB_STEPS = 40                  # timed steps of a sub-record
+ALL_CONFIGS = ("c2", "c3a", "c3b", "c4", "c5")
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by a copy kernel of known size; keyed by workload.  Filled from profiles/*.md.
-MEASURED_TRAFFIC_BYTES = {
-    ("c2", "expert_gemm1"): 1161762918,   # profiles/wsgemm_expert_gemm_c2.md
-    ("c2", "expert_gemm2"): 1162602291,
-    ("c4", "expert_gemm1"): 1627605606,   # profiles/wsgemm_decode_c4.md
-    ("c4", "expert_gemm2"): 1613486490,
+# HBM traffic per launch (bytes) of a workload's longest kernel: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
+# each scaled by what the same counter reads for a plain copy of known size.  Measured in separate runs
+# (profiles/*.md name the commands), not in this process.
+PROFILED_TRAFFIC = {
 }
 
 
-# What a kernel that only reads the same weights in the same access pattern reaches (GB/s), measured with
-# paper_2201_05596_amd/hbm_rate (profiles/hbm_read_ceiling.md): context for roofline.frac, not its denominator.
-MEASURED_READ_CEILING_GBS = {
-    ("c2", "expert_gemm1"): 6850.0,
-    ("c2", "expert_gemm2"): 6910.0,
-}
-
-
-def algorithmic_bytes(cfg, rows):
-    """Bytes the method itself has to move, from the actual per-expert row counts."""
-    d, f, T = cfg.d_model, cfg.d_ffn, cfg.T
+def algorithmic_work(cfg, rows):
+    """Bytes and flops the method itself has to move and compute, from the actual per-expert row counts.
+    Per kernel: the weights and biases it has to read once (unit = one expert with at least one row) and
+    the multiply-adds of its rows (unit = one kept row)."""
+    d, f, T, E = cfg.d_model, cfg.d_ffn, cfg.T, cfg.E
     wb = 4 if cfg.dtype == "f32" else 2
     touched = int((rows > 0).sum())
     kept = int(rows.sum())
-    g1 = touched * (d * f + f) * wb + kept * d * wb + kept * f * wb        # W1,b1 once; rows in; h out
-    g2 = touched * (f * d + d) * wb + kept * f * wb + kept * d * wb        # W2,b2 once; h in; rows out
-    layer = touched * (2 * d * f + f + d) * wb + 2 * T * d * wb + d * cfg.E * 4
-    flops = 4 * d * f * kept + 2 * T * d * cfg.E
+    stage_bytes = {"expert_gemm1": touched * (d * f + f) * wb, "expert_gemm2": touched * (f * d + d) * wb,
+                   "gate_logits": T * d * wb + d * E * 4, "dense_gemm1": (d * f + f) * wb, "dense_gemm2": (f * d + d) * wb}
+    stage_flops = {"expert_gemm1": 2 * d * f * kept, "expert_gemm2": 2 * d * f * kept, "gate_logits": 2 * T * d * E,
+                   "dense_gemm1": 2 * d * f * T, "dense_gemm2": 2 * d * f * T}
+    layer_bytes = touched * (2 * d * f + f + d) * wb + 2 * T * d * wb + d * E * 4
+    layer_flops = 4 * d * f * kept + 2 * T * d * E
     if cfg.residual:
-        layer += (2 * d * f + f + d) * wb
-        flops += 4 * d * f * T
-    return {"expert_gemm1": g1, "expert_gemm2": g2, "layer": layer, "flops": flops,
+        layer_bytes += (2 * d * f + f + d) * wb
+        layer_flops += 4 * d * f * T
+    return {"stage_bytes": stage_bytes, "stage_flops": stage_flops, "layer_bytes": layer_bytes, "layer_flops": layer_flops,
             "touched_experts": touched, "kept_rows": kept}
 
 
-def cpu_baseline(inp, cfg):
-    """The oracle as it stands, one full step of the workload on the host cores."""
+def describe(cfg):
+    return (f"{cfg.name}: T={cfg.T} d_model={cfg.d_model} d_ffn={cfg.d_ffn} E={cfg.E} top_k={cfg.top_k} "
+            f"capacity={cfg.capacity} residual={int(cfg.residual)} seed={cfg.seed}")
+
+
+def time_config(cfg, steps, warmup):
+    """RAMP + warmup untimed steps, then exactly `steps` timed ones.  Returns (record, inputs)."""
+    import torch
+    import paper_2201_05596_amd as moe
+    from workloads import make_inputs
+
+    inp = make_inputs(cfg, "cuda:0")
+    layer = moe.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, cfg.capacity, cfg.dtype, inp.Wg, inp.bg,
+                         inp.W1, inp.b1, inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)
+    for _ in range(RAMP_STEPS + warmup):
+        layer(inp.x)
+    torch.cuda.synchronize()
+
+    moe.moe_profile_select(None)                 # every stage gets its own pair of events ...
+    moe.moe_profile_stride(EVENT_STRIDE)         # ... in every EVENT_STRIDE-th timed step
+    moe.moe_profile_enable((steps + EVENT_STRIDE - 1) // EVENT_STRIDE)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        layer(inp.x)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    names = moe.moe_profile_stage_names()
+    sums = [0.0] * len(names)
+    ncalls = moe.moe_profile_calls()
+    for c in range(ncalls):
+        for i, v in enumerate(moe.moe_profile_elapsed(c)):
+            sums[i] += v
+    moe.moe_profile_enable(0)
+    moe.moe_profile_stride(1)
+    stage_ms = {n: s / max(ncalls, 1) for n, s in zip(names, sums) if s > 0}
+
+    rows = layer.routing["expert_rows"].cpu().numpy()
+    alg = algorithmic_work(cfg, rows)
+    t_hbm = alg["layer_bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = alg["layer_flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) if cfg.dtype == "bf16" else 0.0
+    bound = "mfma" if t_mfma > t_hbm else "hbm"
+    dom = max(stage_ms, key=stage_ms.get) if stage_ms else None
+    dom_ms = stage_ms.get(dom, 0.0) if dom else 0.0
+    if bound == "hbm":
+        work, peak, unit = alg["stage_bytes"].get(dom, 0), HBM_PEAK_GBS, "GB/s"
+        achieved = work / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    else:
+        work, peak, unit = alg["stage_flops"].get(dom, 0), MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        achieved = work / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    traffic = PROFILED_TRAFFIC.get((cfg.name, dom))
+    roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                "traffic": traffic, "traffic_source": "rocprofv3 --pmc, separate run (profiles/)" if traffic else None,
+                "algorithmic_work_per_launch": work, "avg_ms": dom_ms, "timed_launches": ncalls,
+                "t_floor_hbm_us": t_hbm * 1e6, "t_floor_mfma_us": t_mfma * 1e6}
+    layer_gbs = alg["layer_bytes"] / (ms_per_step * 1e-3) / 1e9
+    layer_tflops = alg["layer_flops"] / (ms_per_step * 1e-3) / 1e12
+    rec = {
+        "workload": describe(cfg), "us_per_layer": ms_per_step * 1e3, "tokens_per_s": cfg.T / (ms_per_step * 1e-3),
+        "steps": steps, "warmup": warmup, "kept_rows": alg["kept_rows"], "touched_experts": alg["touched_experts"],
+        "roofline": roofline,
+        "layer_roofline": {"hbm_GBps": layer_gbs, "hbm_frac": layer_gbs / HBM_PEAK_GBS, "mfma_TFLOPs": layer_tflops,
+                           "mfma_frac": layer_tflops / MFMA_BF16_PEAK_TFLOPS, "binding_frac":
+                           (layer_tflops / MFMA_BF16_PEAK_TFLOPS) if bound == "mfma" else layer_gbs / HBM_PEAK_GBS,
+                           "algorithmic_bytes": alg["layer_bytes"], "algorithmic_flops": alg["layer_flops"]},
+        "stage_ms": stage_ms,
+    }
+    return rec, inp, rows
+
+
+def cpu_baseline(inp, cfg, rows, budget_s=12.0):
+    """The oracle as it stands on the host cores, on a bounded sample of the workload: the gate, the dispatch and
+    the combine on all tokens, the expert FFNs on every n-th touched expert (by row count, busiest first) until the
+    time budget is used; the FFN time is scaled by kept rows / sampled rows, the dense branch is timed in full."""
     import numpy as np
     from oracle import moe_oracle as orc
     from workloads.generate import to_f32_numpy
@@ -77,33 +158,51 @@ def cpu_baseline(inp, cfg):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    h = {k: to_f32_numpy(v) for k, v in inp.tensors().items()}
-    steps, total = 0, 0.0
-    while total < 10.0 and steps < 8:          # about 10-20 s of CPU work
+    x = to_f32_numpy(inp.x)
+    Wg, bg = to_f32_numpy(inp.Wg), to_f32_numpy(inp.bg)
+    t0 = time.perf_counter()
+    r = orc.gate(orc.gate_logits(x, Wg, bg), cfg.top_k, cfg.capacity)
+    xe = orc.dispatch(x, r["slot_token"])
+    t_front = time.perf_counter() - t0
+    order = [int(e) for e in np.argsort(-r["expert_rows"], kind="stable") if r["expert_rows"][e] > 0]
+    stride = max(1, len(order) // 8)
+    ye = np.zeros((cfg.E, cfg.capacity, cfg.d_model))
+    t_ffn, sampled_rows, sampled = 0.0, 0, []
+    for e in order[::stride] + [e for i, e in enumerate(order) if i % stride]:
+        if t_ffn > budget_s and sampled:
+            break
+        n = int(r["expert_rows"][e])
+        w = [to_f32_numpy(t[e]) for t in (inp.W1, inp.b1, inp.W2, inp.b2)]       # widening is not timed
         t0 = time.perf_counter()
-        orc.moe_layer_forward(h["x"], h["Wg"], h.get("bg"), h["W1"], h["b1"], h["W2"], h["b2"], cfg.top_k,
-                              cfg.capacity, Wd1=h.get("Wd1"), bd1=h.get("bd1"), Wd2=h.get("Wd2"), bd2=h.get("bd2"))
-        total += time.perf_counter() - t0
-        steps += 1
-    return {"value": cfg.T * steps / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{steps} full step(s) of {cfg.name} ({cfg.T} tokens each), fp64 NumPy, {total:.2f} s"}
+        ye[e, :n] = orc.ffn(xe[e, :n], *w)
+        t_ffn += time.perf_counter() - t0
+        sampled_rows += n
+        sampled.append(e)
+    kept = int(r["expert_rows"].sum())
+    t0 = time.perf_counter()
+    dense = None
+    if cfg.residual:
+        dense = orc.ffn(x, *[to_f32_numpy(t) for t in (inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)])
+    orc.combine(ye, r["expert_idx"], r["slot_idx"], r["gate_w"], dense)
+    t_back = time.perf_counter() - t0
+    total = t_front + t_ffn * kept / max(sampled_rows, 1) + t_back
+    return {"value": cfg.T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{cfg.name}: gate, dispatch, combine{' and dense branch' if cfg.residual else ''} on all {cfg.T} "
+                      f"tokens ({t_front + t_back:.2f} s); expert FFNs of {len(sampled)} of {len(order)} touched experts "
+                      f"= {sampled_rows} of {kept} kept rows ({t_ffn:.2f} s), scaled by rows to {total:.2f} s per step; "
+                      f"fp64 NumPy"}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--config", default="c5", help="headline workload")
+    ap.add_argument("--only", action="store_true", help="time the headline workload only (no sub-records)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--capacity-factor", type=float, default=None, help="experiment: override the workload's capacity factor")
-    ap.add_argument("--no-gate-bias", action="store_true",
-                    help="experiment: drop the workload's gate bias (c5 without its skew: ~512 rows per expert)")
-    ap.add_argument("--no-stage-events", action="store_true",
-                    help="experiment: time the steps without the library's per-stage events (no roofline then)")
-    ap.add_argument("--all-stage-events", action="store_true", help="time every stage (more events, slower step)")
-    ap.add_argument("--event-stride", type=int, default=5,
-                    help="stage events are recorded in every n-th timed step only (the first, the (n+1)-th, ...)")
+    ap.add_argument("--capacity-factor", type=float, default=None,
+                    help="headline workload with another capacity factor (capacity is an input of the library)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -117,43 +216,23 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    import paper_2201_05596_amd as moe
-    from workloads import CONFIGS, make_inputs
+    from workloads import CONFIGS
 
-    cfg = CONFIGS[args.config]
+    head_cfg = CONFIGS[args.config]
     if args.capacity_factor is not None:
-        cfg = cfg.scaled(name=f"{cfg.name}-cf{args.capacity_factor}", capacity_factor=args.capacity_factor)
-    if args.no_gate_bias:
-        cfg = cfg.scaled(name=f"{cfg.name}-nobias", gate_bias_zipf=None)
-    inp = make_inputs(cfg, "cuda:0")
-    layer = moe.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, cfg.capacity, cfg.dtype, inp.Wg, inp.bg,
-                         inp.W1, inp.b1, inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)
-    for _ in range(args.warmup):
-        layer(inp.x)
-    torch.cuda.synchronize()
+        head_cfg = head_cfg.scaled(name=f"{head_cfg.name}-cf{args.capacity_factor}", capacity_factor=args.capacity_factor)
 
-    if not args.no_stage_events:
-        # events only around the two expert GEMMs (the roofline kernel is the longer one): three per timed step, and
-        # only every --event-stride-th step is timed that way (1.5 us per event is 1.5 % of a c2 step)
-        moe.moe_profile_select(None if args.all_stage_events else ["expert_gemm1", "expert_gemm2"])
-        moe.moe_profile_stride(args.event_stride)
-        moe.moe_profile_enable((args.steps + args.event_stride - 1) // args.event_stride)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        layer(inp.x)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    names = moe.moe_profile_stage_names()
-    sums = [0.0] * len(names)
-    ncalls = moe.moe_profile_calls()
-    for c in range(ncalls):
-        for i, v in enumerate(moe.moe_profile_elapsed(c)):
-            sums[i] += v
-    moe.moe_profile_enable(0)
-    stage_ms = {n: s / max(ncalls, 1) for n, s in zip(names, sums) if s > 0}
+    configs = {}
+    if not args.only:
+        for name in ALL_CONFIGS:
+            if name == head_cfg.name:
+                continue
+            rec, inp, _ = time_config(CONFIGS[name], SUB_STEPS, args.warmup)
+            configs[name] = rec
+            del inp
+            torch.cuda.empty_cache()
+    head, inp, rows = time_config(head_cfg, args.steps, args.warmup)
+    configs[head_cfg.name] = head
 
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -163,40 +242,22 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    rows = layer.routing["expert_rows"].cpu().numpy()
-    alg = algorithmic_bytes(cfg, rows)
-    dom = max(("expert_gemm1", "expert_gemm2"), key=lambda n: stage_ms.get(n, 0.0))
-    dom_ms = stage_ms.get(dom, 0.0)
-    achieved = alg[dom] / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
-                "algorithmic_bytes": alg[dom], "avg_ms": dom_ms}
-    ceiling = MEASURED_READ_CEILING_GBS.get((cfg.name, dom))
-    if ceiling:
-        roofline["read_only_kernel_GBps"] = ceiling
-        roofline["frac_of_read_only_kernel"] = achieved / ceiling
-    layer_gbs = alg["layer"] / (ms_per_step * 1e-3) / 1e9
-    layer_tflops = alg["flops"] / (ms_per_step * 1e-3) / 1e12
-
     out = {
-        "metric": "MoE-layer tokens/s at 1 GPU",
-        "value": cfg.T / (ms_per_step * 1e-3),
+        "metric": "MoE-layer tokens/s + us/layer at 1 GPU; % HBM roofline (decode) / % MFMA (prefill)",
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "us_per_layer": ms_per_step * 1e3,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_steps": RAMP_STEPS,
+        "ms_per_step": head["us_per_layer"] * 1e-3, "us_per_layer": head["us_per_layer"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d_model} d_ffn={cfg.d_ffn} E={cfg.E} "
-                               f"top_k={cfg.top_k} capacity={cfg.capacity} residual={int(cfg.residual)} seed={cfg.seed}",
-                   "kept_rows": alg["kept_rows"], "touched_experts": alg["touched_experts"]},
-        "roofline": roofline,
-        "layer_roofline": {"hbm_GBps": layer_gbs, "hbm_frac": layer_gbs / HBM_PEAK_GBS,
-                           "mfma_TFLOPs": layer_tflops, "mfma_frac": layer_tflops / MFMA_BF16_PEAK_TFLOPS,
-                           "algorithmic_bytes": alg["layer"], "algorithmic_flops": alg["flops"]},
-        "stage_ms": stage_ms,
+        "dtype": head_cfg.dtype, "data": "synthetic",
+        "config": {"workload": head["workload"], "kept_rows": head["kept_rows"], "touched_experts": head["touched_experts"]},
+        "roofline": head["roofline"],
+        "layer_roofline": head["layer_roofline"],
+        "stage_ms": head["stage_ms"],
+        "configs": {n: configs[n] for n in ALL_CONFIGS if n in configs} if not args.only else {},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inp, cfg)
+        out["cpu_baseline"] = cpu_baseline(inp, head_cfg, rows)
     print(json.dumps(out))
     return 0
 

@@ -27,6 +27,8 @@
  *   - Non-finite gate logits give unspecified routing.
  *   - Calls on one stream are ordered; two calls that share a workspace and
  *     run concurrently on different streams race.
+ *   - Entry points are called from one host thread at a time (the library
+ *     keeps small host-side caches: kernel attributes, occupancy, profiler).
  */
 #ifndef MOE_H_
 #define MOE_H_

@@ -14,8 +14,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
 SOURCES = ["api.hip", "gate.hip", "gate_bf16.hip", "layout.hip", "gemm_simple.hip", "ffn_mfma.hip", "ffn_tile.hip"]
-# stand-alone measurement programs (source with a main()) -> executables beside the library
-PROGRAMS = {"mfma_rate.hip": os.path.join(HERE, "mfma_rate"), "hbm_rate.hip": os.path.join(HERE, "hbm_rate")}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -24,7 +22,6 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-    *os.environ.get("MOE_HIPCC_EXTRA", "").split(),      # developer experiments (-D...)
 ]
 
 
@@ -47,10 +44,6 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    for src, exe in PROGRAMS.items():
-        r = subprocess.run([HIPCC, *FLAGS, os.path.join(CSRC, src), "-o", exe], capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
     return LIB

@@ -1,6 +1,5 @@
 // C ABI of the library: argument checks, workspace carving and launch sequencing.
 // Every check happens on the host before the first HIP call.
-#include <cstdlib>
 #include <vector>
 
 #include "moe_internal.h"
@@ -83,38 +82,16 @@ struct FfnPlan {
     int NBUF;           // weight super-fragments kept in flight per wave, plus one
 };
 
-// developer tuning knobs (environment, read once), 0 = not set
-enum Knob { KN_NBUF, KN_MT, KN_NW1, KN_NW2, KN_KSPLIT, KN_NOTILE, KN_F32GATE, KN_UNFUSEDGATE, KN_SPREAD, KN_COUNT };
-int tune(Knob k) {
-    static const char* const names[KN_COUNT] = {"MOE_TUNE_NBUF", "MOE_TUNE_MT", "MOE_TUNE_NW1", "MOE_TUNE_NW2",
-                                                "MOE_TUNE_KSPLIT", "MOE_TUNE_NOTILE", "MOE_TUNE_F32GATE",
-                                                "MOE_TUNE_UNFUSEDGATE", "MOE_TUNE_SPREAD"};
-    static int values[KN_COUNT];
-    static bool read = false;
-    if (!read) {
-        for (int i = 0; i < KN_COUNT; ++i) {
-            const char* v = std::getenv(names[i]);
-            values[i] = v ? std::atoi(v) : 0;
-        }
-        read = true;
-    }
-    return values[k];
-}
-
 FfnPlan plan_ffn(const moe_shape_t* s) {
     FfnPlan p{};
     p.mfma = s->dtype == MOE_BF16 && wsgemm_supported(s->d_model, s->d_ffn);
     p.ksplit2 = 1;
-    p.NBUF = tune(KN_NBUF) ? tune(KN_NBUF) : 2;
+    p.NBUF = 2;
     if (!p.mfma) return p;
-    p.tiled = s->capacity > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
-              !tune(KN_NOTILE);
+    p.tiled = s->capacity > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model);
     wsgemm_pick_tile(s->capacity, s->E, s->d_ffn, &p.MT, &p.NW1);
     int mt2;
     wsgemm_pick_tile(s->capacity, s->E, s->d_model, &mt2, &p.NW2);
-    if (tune(KN_MT)) p.MT = tune(KN_MT);
-    if (tune(KN_NW1)) p.NW1 = tune(KN_NW1);
-    if (tune(KN_NW2)) p.NW2 = tune(KN_NW2);
     // GEMM-2 has few output columns; when that leaves the chip short of waves, split K
     const long long touched = s->E < (long long)s->T * s->top_k ? s->E : (long long)s->T * s->top_k;
     const long long m_tiles = (s->capacity + p.MT - 1) / p.MT;
@@ -125,10 +102,6 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
         if (ks > 8) ks = 8;
         if (ks > chunks) ks = chunks;
         p.ksplit2 = (int)(ks < 1 ? 1 : ks);
-    }
-    if (tune(KN_KSPLIT)) {
-        const int chunks = (s->d_ffn + wsgemm_chunk_k(p.MT) - 1) / wsgemm_chunk_k(p.MT);
-        p.ksplit2 = tune(KN_KSPLIT) < chunks ? tune(KN_KSPLIT) : chunks;
     }
     return p;
 }
@@ -171,10 +144,13 @@ int check_ws(const moe_shape_t* s, const void* ws, size_t ws_bytes) {
     return MOE_OK;
 }
 
+// The gate's share of the workspace: the leading regions of the layout (logits, split gate weights, histograms).
+size_t gate_scratch_bytes(const moe_shape_t* s) { return ws_layout(s).expert_idx; }
+
 // gate logits: bf16 tokens go to the bf16 matrix cores when the shape allows, everything else to the fp32 ones
 int run_gate_logits(const moe_shape_t* s, const void* x, const float* Wg, const float* bg, float* logits, void* ws,
                     const WsLayout& L, hipStream_t st) {
-    if (s->dtype == MOE_BF16 && gate_bf16_supported(s->d_model, s->E) && !tune(KN_F32GATE))
+    if (s->dtype == MOE_BF16 && gate_bf16_supported(s->d_model, s->E))
         return launch_gate_logits_bf16(x, Wg, bg, logits, s->T, s->d_model, s->E, at<void>(ws, L.wg_frags), st);
     return launch_gate_logits(x, s->dtype, Wg, bg, logits, s->T, s->d_model, s->E, st);
 }
@@ -186,7 +162,7 @@ int run_gate(const moe_shape_t* s, const void* x, const float* Wg, const float* 
              const WsLayout& L, bool profile, hipStream_t st) {
     int32_t* scratch = at<int32_t>(ws, L.hist);
     int rc;
-    if (s->dtype == MOE_BF16 && gate_bf16_fused_supported(s->T, s->d_model, s->E) && !tune(KN_F32GATE) && !tune(KN_UNFUSEDGATE)) {
+    if (s->dtype == MOE_BF16 && gate_bf16_fused_supported(s->T, s->d_model, s->E)) {
         int tb = 0;
         const int32_t *hist = nullptr, *coarse = nullptr;
         if (profile) prof_pre(ST_LOGITS, st);
@@ -236,7 +212,6 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
-    a.spread = tune(KN_SPREAD);
     prof_pre(ST_GEMM1, st);
     const int rc = p.tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, p.MT, p.NW1, p.NBUF, st);
     prof_mark(ST_GEMM1, st);
@@ -254,7 +229,6 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
     a.gate_w = gate_w; a.top_k = s->top_k;
-    a.spread = tune(KN_SPREAD);
     prof_pre(ST_GEMM2, st);
     if (p.ksplit2 == 1) {
         const int epi = scatter ? EPI_SCATTER : EPI_STORE;
@@ -288,8 +262,7 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
-    const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model) &&
-                       !tune(KN_NOTILE);
+    const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model);
     prof_pre(ST_DENSE1, st);
     int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
     prof_mark(ST_DENSE1, st);
@@ -326,10 +299,11 @@ const char* moe_status_string(int status) {
 
 const char* moe_version(void) { return "0.1"; }
 
-int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
-             int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows, int32_t* slot_token,
-             void* ws, size_t ws_bytes, void* stream) {
-    int rc = check_shape(shape);
+// argument checks shared by moe_gate and moe_gate_noalloc (everything but the scratch memory)
+static int check_gate_args(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
+                           int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows,
+                           int32_t* slot_token) {
+    const int rc = check_shape(shape);
     if (rc != MOE_OK) return rc;
     if (!expert_idx || !slot_idx || !gate_w || !expert_rows || !slot_token) return MOE_ERR_INVALID_ARG;
     if (!x && !logits) return MOE_ERR_INVALID_ARG;
@@ -337,16 +311,30 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
     const void* ptrs[] = {x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token};
     for (const void* p : ptrs)
         if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
-    rc = check_ws(shape, ws, ws_bytes);
-    if (rc != MOE_OK) return rc;
+    return MOE_OK;
+}
 
+// the gate on checked arguments; `ws` holds at least gate_scratch_bytes(shape) bytes
+static int gate_checked(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
+                        int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows,
+                        int32_t* slot_token, void* ws, hipStream_t st) {
     const WsLayout L = ws_layout(shape);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     float* lg = logits ? logits : at<float>(ws, L.logits);
     if (x)
         return run_gate(shape, x, Wg, bg, lg, expert_idx, slot_idx, gate_w, expert_rows, slot_token, nullptr, ws, L, false, st);
     return launch_route(lg, shape->T, shape->E, shape->top_k, shape->capacity, expert_idx, slot_idx, gate_w,
                         expert_rows, slot_token, nullptr, at<int32_t>(ws, L.hist), st);
+}
+
+int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
+             int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows, int32_t* slot_token,
+             void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_gate_args(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token);
+    if (rc != MOE_OK) return rc;
+    rc = check_ws(shape, ws, ws_bytes);
+    if (rc != MOE_OK) return rc;
+    return gate_checked(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws,
+                        static_cast<hipStream_t>(stream));
 }
 
 int moe_dispatch(const moe_shape_t* shape, const void* x, const int32_t* slot_token, const int32_t* expert_rows,
@@ -396,7 +384,7 @@ int moe_combine(const moe_shape_t* shape, const void* ye, const int32_t* expert_
                           shape->capacity, shape->d_model, static_cast<hipStream_t>(stream));
 }
 
-int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, const void* W1,
+static int layer_forward_checked(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, const void* W1,
                       const void* b1, const void* W2, const void* b2, const void* Wd1, const void* bd1, const void* Wd2,
                       const void* bd2, void* out, float* logits_out, int32_t* expert_idx_out, int32_t* slot_idx_out,
                       float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out, void* ws, size_t ws_bytes,
@@ -472,6 +460,18 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     prof_pre(ST_COMBINE, st);
     rc = launch_combine(at<void>(ws, L.ye), dt, expert_idx, slot_idx, gate_w, nullptr, out, T, k, C, d, st);
     prof_mark(ST_COMBINE, st);
+    return rc;
+}
+
+int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, const void* W1,
+                      const void* b1, const void* W2, const void* b2, const void* Wd1, const void* bd1, const void* Wd2,
+                      const void* bd2, void* out, float* logits_out, int32_t* expert_idx_out, int32_t* slot_idx_out,
+                      float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out, void* ws, size_t ws_bytes,
+                      void* stream) {
+    const int rc = layer_forward_checked(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out, logits_out,
+                                         expert_idx_out, slot_idx_out, gate_w_out, expert_rows_out, slot_token_out, ws,
+                                         ws_bytes, stream);
+    g_prof.cur = -1;       // stage events belong to this call only: a later moe_expert_ffn must not add to them
     return rc;
 }
 

@@ -27,7 +27,6 @@
 // Work-groups are numbered so that all row tiles of one (expert, column tile)
 // run on the same XCD back to back and share the weights through that XCD's L2.
 #include "ffn_common.h"
-#include <cstdlib>
 
 namespace moe {
 
@@ -363,8 +362,7 @@ static bool launch_cfg(const WsGemmArgs& a, hipStream_t s) {
     if (total > (1ll << 30)) return false;
     static int resident = 0;                                                       // one per instantiation
     if (!resident) resident = resident_blocks(reinterpret_cast<const void*>(&wsgemm_kernel<MT, NW, EPI, NBUF>), NW * 64);
-    static const bool one_tile_each = std::getenv("MOE_TUNE_NOPERSIST") != nullptr;      // developer experiment
-    const long long blocks = total < resident || one_tile_each ? total : resident;
+    const long long blocks = total < resident ? total : resident;
     hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a, (int)total);
     return true;
 }

@@ -176,7 +176,15 @@ def test_expert_ffn_unequal_experts():
     _check_expert_ffn("bf16", 128, 4096, 16, 200, False, [200, 1, 1, 0, 2, 1, 150, 1, 3, 1, 0, 1, 2, 1, 1, 70])
 
 
-def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows):
+@pytest.mark.parametrize("dtype,d,f,E,C", [("f32", 64, 256, 4, 40), ("bf16", 64, 256, 4, 40), ("bf16", 128, 512, 3, 150)])
+def test_expert_ffn_saturating_gelu(dtype, d, f, E, C):
+    """Pre-activations far into both tails of the tanh-GELU (|z| up to about 40): the kernels evaluate it as
+    z / (1 + exp2(.)), whose exponential overflows to infinity for z << 0 and underflows for z >> 0; the result must
+    still be the oracle's (-0 and z)."""
+    _check_expert_ffn(dtype, d, f, E, C, True, None, w1_std=1.0, b1_std=5.0)
+
+
+def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows, w1_std=0.02, b1_std=0.1):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     g = torch.Generator(device=DEV).manual_seed(d + f)
@@ -187,9 +195,9 @@ def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows):
     if fixed_rows is not None:
         rows = torch.tensor(fixed_rows, dtype=torch.int32, device=DEV)
     xe = torch.randn((E, C, d), generator=g, device=DEV).to(tdt)
-    W1 = (0.02 * torch.randn((E, d, f), generator=g, device=DEV)).to(tdt)
+    W1 = (w1_std * torch.randn((E, d, f), generator=g, device=DEV)).to(tdt)
     W2 = (0.02 * torch.randn((E, f, d), generator=g, device=DEV)).to(tdt)
-    b1 = (0.1 * torch.randn((E, f), generator=g, device=DEV)).to(tdt) if bias else None
+    b1 = (b1_std * torch.randn((E, f), generator=g, device=DEV)).to(tdt) if bias else None
     b2 = (0.1 * torch.randn((E, d), generator=g, device=DEV)).to(tdt) if bias else None
     shape = m.make_shape(8, d, f, E, 1, C, dtype)
     ws = m.alloc_workspace(shape, DEV)
@@ -293,21 +301,17 @@ def test_residual_with_zero_experts_equals_dense_branch():
 
 # ------------------------------------------------------------------ full sizes, as benchmarked
 
-@pytest.mark.parametrize("name", ["c2", "c3a", "c3b", "c4"])
+@pytest.mark.parametrize("name", ["c2", "c3a", "c3b", "c4", "c5"])
 def test_layer_full_size(name):
-    """The benchmark workloads c2, c3a, c3b, c4 at full size, in the launch configuration bench.py times."""
+    """The five benchmark workloads at full size, in the launch configuration bench.py times: routing bit for bit,
+    every output element against the oracle (expert weights widened one expert at a time on the host; config 5
+    holds 17 GB of them, of which the oracle touches the experts that have rows)."""
     print(f"case full {name}", flush=True)
     stats = U.check_layer(make_inputs(CONFIGS[name], DEV), lazy_experts=True)
     print(name, stats, flush=True)
     assert stats["kept"] > 0
-
-
-def test_layer_full_size_c5_sampled():
-    """Config 5 (17 GB of expert weights): routing in full, outputs on sampled tokens."""
-    print("case full c5 (sampled)", flush=True)
-    stats = U.check_layer_sampled(make_inputs(CONFIGS["c5"], DEV))
-    print("c5", stats, flush=True)
-    assert stats["dropped_tokens"] > 0 and stats["tokens_keeping_all_choices"] > 0
+    if name == "c5":
+        assert stats["dropped_tokens"] > 0
 
 
 def test_stage_timing_api():
