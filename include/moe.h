@@ -45,7 +45,8 @@ typedef enum {
     MOE_ERR_INVALID_ARG = -1,  /* null pointer, misaligned pointer, bad size        */
     MOE_ERR_UNSUPPORTED = -2,  /* valid request outside what the kernels cover      */
     MOE_ERR_WORKSPACE = -3,    /* ws is NULL or smaller than moe_workspace_bytes()  */
-    MOE_ERR_HIP = -4           /* a kernel launch failed                            */
+    MOE_ERR_HIP = -4,          /* a kernel launch failed                            */
+    MOE_ERR_SCRATCH_LIMIT = -5 /* moe_gate_noalloc: shape beyond its fixed scratch   */
 } moe_status_t;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
@@ -102,6 +103,25 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
              float* logits, int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
              int32_t* expert_rows, int32_t* slot_token,
              void* ws, size_t ws_bytes, void* stream);
+
+/* moe_gate_noalloc -- moe_gate for callers that cannot allocate device memory or
+ * hand over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * moe_gate, without `ws`: the scratch (logits when `logits` is NULL, the split
+ * gate weights, the block histograms) lives in a fixed array of
+ * moe_gate_noalloc_max_bytes() = 8 MiB inside the library's code object, one
+ * copy per GPU, held until the process ends.  A shape whose gate scratch
+ * (moe_gate_noalloc_bytes(shape); roughly 4*T*E + 6*d*E bytes) exceeds that
+ * returns MOE_ERR_SCRATCH_LIMIT before anything is launched.  The call makes no
+ * allocation and frees nothing; the first call on a device looks the array's
+ * address up once (make that call outside graph capture).  Every call on a GPU
+ * uses that GPU's one array and nothing in it is assumed to survive between
+ * calls: calls that overlap on one GPU (different streams or host threads) race. */
+size_t moe_gate_noalloc_max_bytes(void);
+size_t moe_gate_noalloc_bytes(const moe_shape_t* shape);
+int moe_gate_noalloc(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg,
+                     float* logits, int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
+                     int32_t* expert_rows, int32_t* slot_token, void* stream);
 
 /* moe_dispatch -- first layout transform of Sec. 5.4 (replaces the sparse
  * einsum that sorts tokens by expert): xe[e,c,:] = x[slot_token[e,c],:] for

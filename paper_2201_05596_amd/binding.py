@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
-ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_dispatch",
+ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_gate_noalloc",
+                "moe_gate_noalloc_bytes", "moe_gate_noalloc_max_bytes", "moe_dispatch",
                 "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
                 "moe_profile_stride", "moe_profile_calls",
                 "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
@@ -58,6 +59,12 @@ def load_library() -> ctypes.CDLL:
     lib.moe_version.argtypes = []
     lib.moe_gate.restype = i32
     lib.moe_gate.argtypes = [sp] + [vp] * 9 + [vp, st, vp]
+    lib.moe_gate_noalloc.restype = i32
+    lib.moe_gate_noalloc.argtypes = [sp] + [vp] * 9 + [vp]
+    lib.moe_gate_noalloc_bytes.restype = st
+    lib.moe_gate_noalloc_bytes.argtypes = [sp]
+    lib.moe_gate_noalloc_max_bytes.restype = st
+    lib.moe_gate_noalloc_max_bytes.argtypes = []
     lib.moe_dispatch.restype = i32
     lib.moe_dispatch.argtypes = [sp] + [vp] * 4 + [vp]
     lib.moe_expert_ffn.restype = i32
@@ -140,6 +147,23 @@ def moe_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows
         _ptr(logits, f32), _ptr(expert_idx, i32), _ptr(slot_idx, i32), _ptr(gate_w, f32), _ptr(expert_rows, i32),
         _ptr(slot_token, i32), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check("moe_gate", rc)
+
+
+def moe_gate_noalloc(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token) -> None:
+    i32, f32 = torch.int32, torch.float32
+    rc = load_library().moe_gate_noalloc(
+        ctypes.byref(shape), _ptr(x, _elem(shape) if x is not None else None), _ptr(Wg, f32), _ptr(bg, f32),
+        _ptr(logits, f32), _ptr(expert_idx, i32), _ptr(slot_idx, i32), _ptr(gate_w, f32), _ptr(expert_rows, i32),
+        _ptr(slot_token, i32), _stream())
+    _check("moe_gate_noalloc", rc)
+
+
+def moe_gate_noalloc_bytes(shape: MoeShape) -> int:
+    return int(load_library().moe_gate_noalloc_bytes(ctypes.byref(shape)))
+
+
+def moe_gate_noalloc_max_bytes() -> int:
+    return int(load_library().moe_gate_noalloc_max_bytes())
 
 
 def moe_dispatch(shape, x, slot_token, expert_rows, xe) -> None:

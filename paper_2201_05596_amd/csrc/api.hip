@@ -147,6 +147,26 @@ int check_ws(const moe_shape_t* s, const void* ws, size_t ws_bytes) {
 // The gate's share of the workspace: the leading regions of the layout (logits, split gate weights, histograms).
 size_t gate_scratch_bytes(const moe_shape_t* s) { return ws_layout(s).expert_idx; }
 
+// Scratch of moe_gate_noalloc: one array per GPU, inside the library's code object, so that the call needs no
+// workspace from its caller and no allocation.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels get the device address that call returns, looked up once per device.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+void* g_static_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    if (!g_static_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) return MOE_ERR_HIP;
+        g_static_scratch_ptr[dev] = p;
+    }
+    *out = g_static_scratch_ptr[dev];
+    return MOE_OK;
+}
+
 // gate logits: bf16 tokens go to the bf16 matrix cores when the shape allows, everything else to the fp32 ones
 int run_gate_logits(const moe_shape_t* s, const void* x, const float* Wg, const float* bg, float* logits, void* ws,
                     const WsLayout& L, hipStream_t st) {
@@ -293,6 +313,7 @@ const char* moe_status_string(int status) {
         case MOE_ERR_UNSUPPORTED: return "unsupported shape";
         case MOE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case MOE_ERR_HIP: return "HIP launch failed";
+        case MOE_ERR_SCRATCH_LIMIT: return "shape needs more scratch than the no-allocation entry point holds";
         default: return "unknown status";
     }
 }
@@ -334,6 +355,26 @@ int moe_gate(const moe_shape_t* shape, const void* x, const float* Wg, const flo
     rc = check_ws(shape, ws, ws_bytes);
     if (rc != MOE_OK) return rc;
     return gate_checked(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws,
+                        static_cast<hipStream_t>(stream));
+}
+
+size_t moe_gate_noalloc_max_bytes(void) { return kStaticScratchBytes; }
+
+size_t moe_gate_noalloc_bytes(const moe_shape_t* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return gate_scratch_bytes(shape);
+}
+
+int moe_gate_noalloc(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,
+                     int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows, int32_t* slot_token,
+                     void* stream) {
+    int rc = check_gate_args(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token);
+    if (rc != MOE_OK) return rc;
+    if (gate_scratch_bytes(shape) > kStaticScratchBytes) return MOE_ERR_SCRATCH_LIMIT;
+    void* scratch = nullptr;
+    rc = static_scratch(&scratch);
+    if (rc != MOE_OK) return rc;
+    return gate_checked(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, scratch,
                         static_cast<hipStream_t>(stream));
 }
 
