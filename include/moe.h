@@ -51,9 +51,16 @@ typedef enum {
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
 
+/* Bits of moe_shape_t.flags. */
+enum {
+    /* W1, W2 (and Wd1, Wd2) are not the plain [E,d,f] / [E,f,d] arrays but the
+     * buffers moe_pack_weights() wrote from them (bf16 only). */
+    MOE_FLAG_PACKED_WEIGHTS = 1
+};
+
 /* Shape of one MoE layer.  Limits: T >= 1, 1 <= E <= 1024, top_k in {1,2} and
  * <= E, capacity >= 1, T*top_k and E*capacity below 2^31; d_model and d_ffn
- * multiples of 8 (bf16) or 4 (f32).  `flags` must be 0. */
+ * multiples of 8 (bf16) or 4 (f32).  `flags`: 0 or MOE_FLAG_* bits. */
 typedef struct {
     int32_t T;         /* tokens (paper: S)                                    */
     int32_t d_model;   /* hidden size (paper: M)                               */
@@ -63,7 +70,7 @@ typedef struct {
     int32_t capacity;  /* rows per expert (paper: c_e)                         */
     int32_t dtype;     /* moe_dtype_t                                          */
     int32_t residual;  /* 1: Residual-MoE (dense MLP branch added), else 0     */
-    int32_t flags;     /* reserved, 0                                          */
+    int32_t flags;     /* MOE_FLAG_* bits, 0 = plain weights                   */
 } moe_shape_t;
 
 /* Upper bound, in bytes, of the workspace any entry point needs for this
@@ -75,6 +82,21 @@ const char* moe_status_string(int status);
 
 /* Library version, "major.minor". */
 const char* moe_version(void);
+
+/* moe_pack_weights -- optional one-time re-tiling of bf16 FFN weights for the
+ * matrix cores (inference weights do not change between calls; Sec. 5.1: what
+ * an inference step costs is reading the parameters).  W is a plain row-major
+ * [G,K,N] array (W1: G=E, K=d_model, N=d_ffn; W2: G=E, K=d_ffn, N=d_model; the
+ * dense branch: G=1); `packed` receives moe_packed_weights_bytes(G,K,N) bytes
+ * (K rounded up to 32, N to 128, zero filled) in which every 16 bytes are 8
+ * consecutive k of one column, in the order the matrix instructions consume
+ * them.  Pass the packed buffers as W1/W2/Wd1/Wd2 together with
+ * MOE_FLAG_PACKED_WEIGHTS in shape.flags (all of a call's FFN weights packed,
+ * or none).  The plain layout stays the default input of every entry point;
+ * results are the same either way up to fp32 summation order.  K and N must be
+ * multiples of 8.  moe_packed_weights_bytes returns 0 for sizes it rejects. */
+size_t moe_packed_weights_bytes(int32_t G, int32_t K, int32_t N);
+int moe_pack_weights(int32_t G, int32_t K, int32_t N, const void* W, void* packed, void* stream);
 
 /* moe_gate -- the fused gating function of Sec. 5.4: gate logits, softmax,
  * top-k, the cumulative sum that gives each token its position inside its

@@ -20,7 +20,9 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
-ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_gate", "moe_gate_noalloc",
+MOE_FLAG_PACKED_WEIGHTS = 1
+ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_packed_weights_bytes",
+                "moe_pack_weights", "moe_gate", "moe_gate_noalloc",
                 "moe_gate_noalloc_bytes", "moe_gate_noalloc_max_bytes", "moe_dispatch",
                 "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
                 "moe_profile_stride", "moe_profile_calls",
@@ -57,6 +59,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_status_string.argtypes = [i32]
     lib.moe_version.restype = ctypes.c_char_p
     lib.moe_version.argtypes = []
+    lib.moe_packed_weights_bytes.restype = st
+    lib.moe_packed_weights_bytes.argtypes = [i32, i32, i32]
+    lib.moe_pack_weights.restype = i32
+    lib.moe_pack_weights.argtypes = [i32, i32, i32, vp, vp, vp]
     lib.moe_gate.restype = i32
     lib.moe_gate.argtypes = [sp] + [vp] * 9 + [vp, st, vp]
     lib.moe_gate_noalloc.restype = i32
@@ -91,12 +97,13 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
-def make_shape(T: int, d_model: int, d_ffn: int, E: int, top_k: int, capacity: int, dtype, residual: bool = False) -> MoeShape:
+def make_shape(T: int, d_model: int, d_ffn: int, E: int, top_k: int, capacity: int, dtype, residual: bool = False,
+               flags: int = 0) -> MoeShape:
     if isinstance(dtype, torch.dtype):
         dtype = {torch.float32: MOE_F32, torch.bfloat16: MOE_BF16}[dtype]
     elif isinstance(dtype, str):
         dtype = {"f32": MOE_F32, "bf16": MOE_BF16}[dtype]
-    return MoeShape(T, d_model, d_ffn, E, top_k, capacity, int(dtype), int(bool(residual)), 0)
+    return MoeShape(T, d_model, d_ffn, E, top_k, capacity, int(dtype), int(bool(residual)), int(flags))
 
 
 def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> Optional[int]:
@@ -138,6 +145,21 @@ def alloc_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:
     if n == 0:
         raise MoeError("moe_workspace_bytes", -1, "invalid shape")
     return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def moe_packed_weights_bytes(G: int, K: int, N: int) -> int:
+    return int(load_library().moe_packed_weights_bytes(int(G), int(K), int(N)))
+
+
+def moe_pack_weights(W: torch.Tensor) -> torch.Tensor:
+    """Packed copy of bf16 weights [G,K,N] (or [K,N]) for MOE_FLAG_PACKED_WEIGHTS; torch owns the new buffer."""
+    G, K, N = (1, *W.shape) if W.dim() == 2 else W.shape
+    nbytes = moe_packed_weights_bytes(G, K, N)
+    if nbytes == 0:
+        raise MoeError("moe_packed_weights_bytes", -2, "unsupported size")
+    packed = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=W.device)
+    _check("moe_pack_weights", load_library().moe_pack_weights(G, K, N, _ptr(W, torch.bfloat16), _ptr(packed), _stream()))
+    return packed
 
 
 def moe_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws) -> None:

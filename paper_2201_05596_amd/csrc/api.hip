@@ -64,7 +64,8 @@ int check_shape(const moe_shape_t* s) {
     if (s->top_k < 1 || s->top_k > s->E) return MOE_ERR_INVALID_ARG;
     if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
     if (s->residual != 0 && s->residual != 1) return MOE_ERR_INVALID_ARG;
-    if (s->flags != 0) return MOE_ERR_INVALID_ARG;
+    if (s->flags & ~MOE_FLAG_PACKED_WEIGHTS) return MOE_ERR_INVALID_ARG;
+    if ((s->flags & MOE_FLAG_PACKED_WEIGHTS) && s->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
     if (s->top_k > 2 || s->E > 1024) return MOE_ERR_UNSUPPORTED;
     const int mult = s->dtype == MOE_F32 ? 4 : 8;
     if (s->d_model % mult || s->d_ffn % mult) return MOE_ERR_UNSUPPORTED;
@@ -230,6 +231,7 @@ int run_expert_gemm1(const moe_shape_t* s, const FfnPlan& p, const void* xin, co
                      hipStream_t st) {
     WsGemmArgs a{};
     a.A = u16(xin); a.B = u16(W1); a.bias = u16(b1); a.rows = rows; a.order = order; a.row_map = row_map;
+    a.packed = s->flags & MOE_FLAG_PACKED_WEIGHTS;
     a.max_rows = s->capacity; a.map_stride = s->capacity; a.G = s->E; a.K = s->d_model; a.N = s->d_ffn;
     a.a_group_stride = s->capacity; a.out = u16(h); a.o_group_stride = s->capacity; a.ksplit = 1;
     prof_pre(ST_GEMM1, st);
@@ -245,6 +247,7 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
                      const float* gate_w, void* dst, float* partial, hipStream_t st) {
     WsGemmArgs a{};
     a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.order = order; a.row_map = nullptr;
+    a.packed = s->flags & MOE_FLAG_PACKED_WEIGHTS;
     a.max_rows = s->capacity; a.G = s->E; a.K = s->d_ffn; a.N = s->d_model;
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;
     a.scatter_map = slot_token; a.scatter_stride = s->capacity; a.zero_slot_idx = slot_idx; a.T = s->T;
@@ -280,11 +283,12 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     int MT, NW;
     WsGemmArgs a{};
     a.A = u16(x); a.B = u16(Wd1); a.bias = u16(bd1); a.fixed_rows = s->T; a.max_rows = s->T; a.G = 1;
+    a.packed = s->flags & MOE_FLAG_PACKED_WEIGHTS;
     a.K = s->d_model; a.N = s->d_ffn; a.out = u16(hd); a.ksplit = 1;
     wsgemm_pick_tile(s->T, 1, s->d_ffn, &MT, &NW);
     const bool tiled = s->T > 64 && tgemm_supported(s->d_model, s->d_ffn) && tgemm_supported(s->d_ffn, s->d_model);
     prof_pre(ST_DENSE1, st);
-    int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 4, st);
+    int rc = tiled ? launch_tgemm(a, EPI_GELU, st) : launch_wsgemm(a, EPI_GELU, MT, NW, 2, st);
     prof_mark(ST_DENSE1, st);
     if (rc != MOE_OK) return rc;
     a.A = u16(hd); a.B = u16(Wd2); a.bias = u16(bd2); a.K = s->d_ffn; a.N = s->d_model; a.out = u16(out);
@@ -292,7 +296,7 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     a.C = s->capacity;
     wsgemm_pick_tile(s->T, 1, s->d_model, &MT, &NW);
     prof_pre(ST_DENSE2, st);
-    rc = tiled ? launch_tgemm(a, EPI_COMBINE, st) : launch_wsgemm(a, EPI_COMBINE, MT, NW, 4, st);
+    rc = tiled ? launch_tgemm(a, EPI_COMBINE, st) : launch_wsgemm(a, EPI_COMBINE, MT, NW, 2, st);
     prof_mark(ST_DENSE2, st);
     return rc;
 }
@@ -318,7 +322,18 @@ const char* moe_status_string(int status) {
     }
 }
 
-const char* moe_version(void) { return "0.1"; }
+const char* moe_version(void) { return "0.2"; }
+
+size_t moe_packed_weights_bytes(int32_t G, int32_t K, int32_t N) {
+    if (G < 1 || K < 8 || N < 8 || K % 8 || N % 8) return 0;
+    return packed_weight_elems(G, K, N) * 2;
+}
+
+int moe_pack_weights(int32_t G, int32_t K, int32_t N, const void* W, void* packed, void* stream) {
+    if (G < 1 || K < 8 || N < 8 || !W || !packed || !aligned16(W) || !aligned16(packed)) return MOE_ERR_INVALID_ARG;
+    if (K % 8 || N % 8) return MOE_ERR_UNSUPPORTED;
+    return launch_pack_weights(u16(W), u16(packed), G, K, N, static_cast<hipStream_t>(stream));
+}
 
 // argument checks shared by moe_gate and moe_gate_noalloc (everything but the scratch memory)
 static int check_gate_args(const moe_shape_t* shape, const void* x, const float* Wg, const float* bg, float* logits,

@@ -90,7 +90,7 @@ __device__ __forceinline__ WsWork ws_find_work(const WsGemmArgs& a, const WsGeo&
 // One tile: prologue (row table, first activation chunk), the weight stream down K, epilogue.  `nxt` is the
 // work-group's next tile OF THE SAME GEMM (has_next false if there is none): the fragments fetched ahead at the
 // end of this tile are its first ones, and `primed` tells the next call that they are in `raw` already.
-template <int MT, int NW, int EPI, int NBUF>
+template <int MT, int NW, int EPI, int NBUF, bool PACKED>
 __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, const WsWork& cur, const WsWork& nxt,
                                         const bool has_next, uint4 (&raw)[NBUF][8], bool& primed, char* lds,
                                         long long* arow_sh, int* tok_sh, float* gw_sh) {
@@ -112,11 +112,19 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
     const int n_lane_raw = lane_col(cur.nt);
     const bool col_ok = n_lane_raw < a.N;
     const int n_lane = col_ok ? n_lane_raw : a.N - 8;             // clamp: loads stay in bounds, never stored
-    const uint16_t* Bg = a.B + (size_t)g * a.K * a.N + n_lane;
+    // K-major weights: 8 columns n_lane.. of a k-row.  Packed weights: the wave's 128-column group (column tile nt,
+    // wave w), whose eight fragments of one 32-deep k-block are 8 KB in a row; a lane takes 16 bytes of each.
+    const int p_kb = (a.K + 31) / 32, p_ng = (a.N + 127) / 128;
+    auto packed_base = [&](int gg, int nt) {
+        const int grp = min(nt * NW + w, p_ng - 1);               // clamped like the column: loaded, never stored
+        return a.B + ((size_t)gg * p_kb * p_ng + grp) * 4096 + lane * 8;
+    };
+    const uint16_t* Bg = PACKED ? packed_base(g, cur.nt) : a.B + (size_t)g * a.K * a.N + n_lane;
     // everything the epilogue needs from memory is fetched here: a load issued after the weight
     // fragments that run ahead into the next tile could only be waited for together with them
     const uint4 bias_raw = EPI != EPI_PARTIAL ? load_bias_raw(a, g, n_lane) : make_uint4(0, 0, 0, 0);
-    const uint16_t* Bn = a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
+    const uint16_t* Bn = PACKED ? packed_base(has_next ? nxt.g : g, has_next ? nxt.nt : cur.nt)
+                                : a.B + (size_t)(has_next ? nxt.g : g) * a.K * a.N + min(lane_col(has_next ? nxt.nt : cur.nt), a.N - 8);
     const int k_end_pad = ch_end * KC;                          // first k that belongs to the next tile
     const int k_next = has_next ? nxt.ch_beg * KC : 0;
 
@@ -125,12 +133,21 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
     // the activation side; rows from k_end_pad on are the first rows of the NEXT tile of this work-group,
     // so the fragments fetched ahead at the end of a tile are the next tile's first ones and the weight
     // stream does not stop for the epilogue (without a next tile they re-read this tile's first rows).
+    // Packed: dst[j] is fragment j of k-block k0/32 (k0 is a multiple of 32), same rules per k-block.
     auto b_load = [&](uint4 (&dst)[8], int k0) {
-        const int kk = k0 + kg * 8;
-        const bool own = kk < k_end_pad;
-        const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
+        if constexpr (PACKED) {
+            const bool own = k0 < k_end_pad;
+            const int kb = min((own ? k0 : k0 - k_end_pad + k_next) / kSF, p_kb - 1);
+            const uint16_t* p = (own ? Bg : Bn) + (size_t)kb * p_ng * 4096;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
+            for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + j * 512);
+        } else {
+            const int kk = k0 + kg * 8;
+            const bool own = kk < k_end_pad;
+            const uint16_t* p = (own ? Bg : Bn) + (size_t)min(own ? kk : kk - k_end_pad + k_next, a.K - 8) * a.N;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dst[j] = load_stream16(p + (size_t)j * a.N);
+        }
     };
     // The tile's first weight fragments go out before anything else (unless the previous tile already fetched
     // them): the row table and the epilogue inputs below cost another memory round trip or two, which the
@@ -194,7 +211,12 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
             bf16x8_t blo, bhi;
-            b_frag_pair(src, qq, blo, bhi);
+            if constexpr (PACKED) {
+                blo = __builtin_bit_cast(bf16x8_t, src[2 * qq]);
+                bhi = __builtin_bit_cast(bf16x8_t, src[2 * qq + 1]);
+            } else {
+                b_frag_pair(src, qq, blo, bhi);
+            }
 #pragma unroll
             for (int ms = 0; ms < MSUB; ++ms) {
                 acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
@@ -259,7 +281,7 @@ __device__ __forceinline__ void ws_tile(const WsGemmArgs& a, const WsGeo& geo, c
     }
 }
 
-template <int MT, int NW, int EPI, int NBUF>
+template <int MT, int NW, int EPI, int NBUF, bool PACKED>
 __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, const int total_blocks) {
     typedef WsTile<MT, NW> TC;
     __shared__ __attribute__((aligned(16))) char lds[TC::LDS_A];
@@ -279,7 +301,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, con
     WsWork cur = ws_find_work<MT, EPI>(a, geo, blockIdx.x, total_blocks, gridDim.x);
     while (cur.vb < total_blocks) {
         const WsWork nxt = ws_find_work<MT, EPI>(a, geo, cur.vb + gridDim.x, total_blocks, gridDim.x);
-        ws_tile<MT, NW, EPI, NBUF>(a, geo, cur, nxt, nxt.vb < total_blocks, raw, primed, lds, arow_sh, tok_sh, gw_sh);
+        ws_tile<MT, NW, EPI, NBUF, PACKED>(a, geo, cur, nxt, nxt.vb < total_blocks, raw, primed, lds, arow_sh, tok_sh, gw_sh);
         cur = nxt;
     }
 }
@@ -354,17 +376,21 @@ static int resident_blocks(const void* kernel, int threads) {
     return per_cu * cus / kXcd * kXcd;
 }
 
-template <int MT, int NW, int EPI, int NBUF>
-static bool launch_cfg(const WsGemmArgs& a, hipStream_t s) {
+template <int MT, int NW, int EPI, int NBUF, bool PACKED>
+static bool launch_cfg_p(const WsGemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + NW * kWaveCols - 1) / (NW * kWaveCols);
     const int m_tiles = (a.max_rows + MT - 1) / MT;
     const long long total = tile_grid_blocks(a, n_tiles, m_tiles * a.ksplit);      // a multiple of the XCD count
     if (total > (1ll << 30)) return false;
     static int resident = 0;                                                       // one per instantiation
-    if (!resident) resident = resident_blocks(reinterpret_cast<const void*>(&wsgemm_kernel<MT, NW, EPI, NBUF>), NW * 64);
+    if (!resident) resident = resident_blocks(reinterpret_cast<const void*>(&wsgemm_kernel<MT, NW, EPI, NBUF, PACKED>), NW * 64);
     const long long blocks = total < resident ? total : resident;
-    hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a, (int)total);
+    hipLaunchKernelGGL((wsgemm_kernel<MT, NW, EPI, NBUF, PACKED>), dim3((unsigned)blocks), dim3(NW * 64), 0, s, a, (int)total);
     return true;
+}
+template <int MT, int NW, int EPI, int NBUF>
+static bool launch_cfg(const WsGemmArgs& a, hipStream_t s) {
+    return a.packed ? launch_cfg_p<MT, NW, EPI, NBUF, true>(a, s) : launch_cfg_p<MT, NW, EPI, NBUF, false>(a, s);
 }
 
 template <int EPI>
@@ -372,9 +398,6 @@ static bool launch_epi(const WsGemmArgs& a, int MT, int NW, int NBUF, hipStream_
 #define MOE_WS_CASE(mt, nw, nb) if (MT == mt && NW == nw && NBUF == nb) return launch_cfg<mt, nw, EPI, nb>(a, s);
     MOE_WS_CASE(16, 4, 2) MOE_WS_CASE(16, 2, 2) MOE_WS_CASE(32, 4, 2) MOE_WS_CASE(32, 2, 2)
     MOE_WS_CASE(64, 4, 2) MOE_WS_CASE(64, 2, 2)
-    MOE_WS_CASE(16, 4, 4) MOE_WS_CASE(16, 2, 4) MOE_WS_CASE(32, 4, 4) MOE_WS_CASE(32, 2, 4)
-    MOE_WS_CASE(64, 4, 4) MOE_WS_CASE(64, 2, 4)
-    MOE_WS_CASE(16, 1, 4) MOE_WS_CASE(32, 1, 4) MOE_WS_CASE(64, 1, 4)
 #undef MOE_WS_CASE
     return false;
 }

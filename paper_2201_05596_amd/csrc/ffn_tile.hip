@@ -68,7 +68,7 @@ template <int WM, int NWM, int NS_, int WN> struct TileCfg {
     static constexpr int LDS_BYTES = RING + BM * 8;
 };
 
-template <int WM, int NWM, int NSX, int EPI, int WN>
+template <int WM, int NWM, int NSX, int EPI, int WN, bool PACKED>
 __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
     typedef TileCfg<WM, NWM, NSX, WN> Cfg;
     constexpr int TBN = Cfg::TBN, NCF = WN / 16;               // column fragments (= columns per lane) of a wave
@@ -117,6 +117,14 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     constexpr int NS = LIGHT ? Cfg::L_NS : Cfg::NS, STAGE = LIGHT ? Cfg::L_STAGE : Cfg::STAGE;
     constexpr int A_BYTES = LIGHT ? Cfg::L_A_BYTES : Cfg::A_BYTES, NIA = !LOADA ? 0 : LIGHT ? 1 : Cfg::NIA;
     constexpr int PER_STAGE = NIA + NIB;                       // loads per wave and stage
+    // The hand-written waits below count on this: every issue() puts exactly PER_STAGE direct loads of this wave in
+    // flight (its two loops have compile-time trip counts NIA and NIB, no lane or wave skips one), loads complete in
+    // order, NS - 1 stages are issued before the first wait, and each step issues one stage after waiting for all
+    // but the NS - 3 youngest.  vmcnt is a 6-bit counter.
+    static_assert(NS >= 3, "the ring needs a stage being read, one landing and one in flight");
+    static_assert(PER_STAGE >= 1 && (NS - 1) * PER_STAGE < 64, "outstanding direct loads must fit the vmcnt field");
+    static_assert(NIB * Cfg::NWAVES * 1024 == Cfg::B_BYTES, "the waves' weight loads tile a stage exactly");
+    static_assert(!LOADA || NIA * Cfg::NWAVES * 1024 == A_BYTES, "the waves' activation loads tile a stage exactly");
 
     // ---- per-lane sources of the direct loads (fixed for the whole k-loop) ---------------------------
     // activations: wave w, load i copies rows (w*NIA + i)*16 .. +15; lane L -> row +L/4, slot L%4
@@ -136,9 +144,16 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     static_assert(WN == 128 || NIB == 1, "the half swap assumes one weight load per wave and stage");
     const int b_row = w * NIB * RPI + lane / LPR;
     const int b_piece = (lane % LPR) ^ (WN == 64 ? ((b_row >> 3) & 1) * 8 : 0);
-    const uint16_t* b_src = a.B + (size_t)g * a.K * a.N + (size_t)b_row * a.N +
-                            min(n0 + b_piece * 8, a.N - 8);           // clamped column: loaded, never stored
-    const size_t b_step2 = (size_t)RPI * a.N;
+    // Packed weights: a stage of the tile is TBN/16 ready-made fragments of 1 KB; load i of wave w copies fragment
+    // w*NIB + i (all of one wave's fragments lie in one 128-column group: NIB divides 8), whole and in place.
+    static_assert(8 % NIB == 0, "a wave's weight loads stay inside one 128-column group");
+    const int p_ng = (a.N + 127) / 128;
+    const int p_grp = min(n0 / 128 + (w * NIB) / 8, p_ng - 1);             // clamped group: loaded, never stored
+    const uint16_t* b_src = PACKED
+        ? a.B + (((size_t)g * (a.K / kTK) * p_ng + p_grp) * 8 + (w * NIB) % 8) * 512 + lane * 8
+        : a.B + (size_t)g * a.K * a.N + (size_t)b_row * a.N + min(n0 + b_piece * 8, a.N - 8);   // clamped column
+    const size_t b_step2 = PACKED ? (size_t)512 : (size_t)RPI * a.N;        // from one load of a stage to the next
+    const size_t b_kstep = PACKED ? (size_t)p_ng * 4096 : (size_t)kTK * a.N;   // from one stage to the next
     const int steps = a.K / kTK;
     auto issue = [&](int step) {                                // all loads of one stage, this wave's share
         const int st = min(step, steps - 1);                    // past the end: harmless re-read, keeps the count uniform
@@ -147,7 +162,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
 #pragma unroll
         for (int i = 0; i < NIA; ++i)
             dma16(a_src[i] + k0, __builtin_amdgcn_readfirstlane(base + (w * NIA + i) * 1024));
-        const uint16_t* bp = b_src + (size_t)k0 * a.N;
+        const uint16_t* bp = b_src + (size_t)st * b_kstep;
 #pragma unroll
         for (int i = 0; i < NIB; ++i)
             dma16(bp + i * b_step2, __builtin_amdgcn_readfirstlane(base + A_BYTES + (w * NIB + i) * 1024));
@@ -162,20 +177,27 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     // A fragment of sub-tile ms: row R = wm*WM + ms*16 + c, k-piece kg -> slot kg ^ a_swizzle(R);
     // a_swizzle(R) == a_swizzle(c) because the other terms are multiples of 16
     const int a_lane = (wm * WM + c) * 64 + ((kg ^ a_swizzle(c)) * 16);
-    const int b_lane = A_BYTES + (kg * 8) * (TBN * 2) + (((wn * WN + c * NCF) * 2) ^ (WN == 64 ? (kg & 1) * 128 : 0));
+    const int b_lane = PACKED ? A_BYTES + wn * (NCF * 1024) + lane * 16
+                              : A_BYTES + (kg * 8) * (TBN * 2) + (((wn * WN + c * NCF) * 2) ^ (WN == 64 ? (kg & 1) * 128 : 0));
 
-    // operand fragments of one stage in registers: per k-row the lane's NCF columns (16 or 8 bytes), and the
-    // activation fragments
+    // operand fragments of one stage in registers.  K-major weights: per k-row the lane's NCF columns (16 or 8
+    // bytes), transposed in registers before use; packed weights: the NCF fragments as they are.
     typedef typename std::conditional<NCF == 8, uint4, uint2>::type BRaw;
     struct Frags {
-        BRaw braw[8];
+        BRaw braw[PACKED ? 1 : 8];
+        bf16x8_t bf[PACKED ? NCF : 1];
         bf16x8_t af[NA];
     };
     auto read_frags = [&](Frags& f, int buf) {
         if (ACT == 0) return;
         const char* base = lds + buf * STAGE;
+        if constexpr (PACKED) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const BRaw*>(base + b_lane + j * (TBN * 2));
+            for (int j = 0; j < NCF; ++j) f.bf[j] = *reinterpret_cast<const bf16x8_t*>(base + b_lane + j * 1024);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f.braw[j] = *reinterpret_cast<const BRaw*>(base + b_lane + j * (TBN * 2));
+        }
 #pragma unroll
         for (int ms = 0; ms < ACT; ++ms) f.af[ms] = *reinterpret_cast<const bf16x8_t*>(base + a_lane + ms * 16 * 64);
     };
@@ -186,6 +208,13 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     };
     auto mma = [&](const Frags& f) {
         if (ACT == 0) return;
+        if constexpr (PACKED) {
+#pragma unroll
+            for (int j = 0; j < NCF; ++j)
+#pragma unroll
+                for (int ms = 0; ms < ACT; ++ms)
+                    acc[ms][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], f.bf[j], acc[ms][j], 0, 0, 0);
+        } else {
 #pragma unroll
         for (int qq = 0; qq < NCF / 2; ++qq) {
             // 8 k-rows x 2 columns of 16-bit values -> two fragments (v_perm_b32), as in the streaming kernel
@@ -203,6 +232,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
                 acc[ms][2 * qq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], blo, acc[ms][2 * qq], 0, 0, 0);
                 acc[ms][2 * qq + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.af[ms], bhi, acc[ms][2 * qq + 1], 0, 0, 0);
             }
+        }
         }
     };
 
@@ -230,7 +260,7 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
         // products (c3a GEMM-1: 91 -> 85 us) and nothing on K = 4096 ones; the store kernel with the same pins loses
         // 2 % on c5's K = 16384 tiles.
         if (EPI == EPI_GELU && ACT == MSUB && !LIGHT) {
-            constexpr int READS = 8 + ACT, MFMAS = NCF * ACT, PER = MFMAS / READS > 0 ? MFMAS / READS : 1;
+            constexpr int READS = (PACKED ? NCF : 8) + ACT, MFMAS = NCF * ACT, PER = MFMAS / READS > 0 ? MFMAS / READS : 1;
             constexpr int GROUPS = MFMAS / PER < READS ? MFMAS / PER : READS;
 #pragma unroll
             for (int i = 0; i < GROUPS; ++i) {
@@ -250,7 +280,9 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     wait_vmcnt<0>();                      // drain the over-issued tail loads before LDS is released
 
     // ---- epilogue ------------------------------------------------------------------------------
-    const int n_lane = n0 + wn * WN + c * NCF;
+    // packed weights, 64-column waves: wave wn holds fragments 4wn..4wn+3 of the tile's one 128-column group,
+    // i.e. columns 8c + 4wn + i of it
+    const int n_lane = PACKED && WN == 64 ? n0 + c * 8 + wn * 4 : n0 + wn * WN + c * NCF;
     if (ACT == 0 || n_lane >= a.N) return;
     float bias[NCF];
     {
@@ -313,23 +345,30 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     }
 }
 
-template <int WM, int NWM, int NSX, int EPI, int WN>
-static int launch_t(const WsGemmArgs& a, hipStream_t s) {
+template <int WM, int NWM, int NSX, int EPI, int WN, bool PACKED>
+static int launch_tp(const WsGemmArgs& a, hipStream_t s) {
     constexpr int BM = NWM * WM, TBN = 2 * WN;
     const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
     const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
     if (blocks > (1ll << 30)) return MOE_ERR_UNSUPPORTED;        // block indices are ints in the kernel
     const size_t smem = TileCfg<WM, NWM, NSX, WN>::LDS_BYTES;
+    static_assert(TileCfg<WM, NWM, NSX, WN>::LDS_BYTES <= 160 * 1024, "a work-group's ring must fit one CU's LDS");
+    static_assert(TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU * TileCfg<WM, NWM, NSX, WN>::LDS_BYTES <= 160 * 1024,
+                  "the promised work-groups per CU must fit its LDS together");
     static bool attr_set = false;            // one flag per instantiation
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, NSX, EPI, WN>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tgemm_kernel<WM, NWM, NSX, EPI, WN, PACKED>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI, WN>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
+    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI, WN, PACKED>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+template <int WM, int NWM, int NSX, int EPI, int WN>
+static int launch_t(const WsGemmArgs& a, hipStream_t s) {
+    return a.packed ? launch_tp<WM, NWM, NSX, EPI, WN, true>(a, s) : launch_tp<WM, NWM, NSX, EPI, WN, false>(a, s);
 }
 
 // Tile shapes.  256 x 256 (4 x 2 waves of 64 x 128: the accumulators take 128 registers, which the compiler updates

@@ -131,7 +131,8 @@ enum WsEpilogue {
 };
 struct WsGemmArgs {
     const uint16_t* A;         // activations, leading dimension K
-    const uint16_t* B;         // [G, K, N]
+    const uint16_t* B;         // [G, K, N], or the same weights in fragment order (packed != 0)
+    int32_t packed;            // B is [G, ceil(K/32), ceil(N/128), 8, 64, 8] as written by launch_pack_weights
     const uint16_t* bias;      // [G, N] or nullptr
     const int32_t* rows;       // [G] device row counts or nullptr -> fixed_rows
     const int32_t* order;      // [G + 1] groups in launch order (busiest first), then the tile-dealing flag; or nullptr -> identity
@@ -142,7 +143,7 @@ struct WsGemmArgs {
     uint16_t* out;             // leading dimension N
     long long o_group_stride;
     int32_t ksplit;            // >= 1; > 1 only with EPI_PARTIAL
-    int32_t spread;            // tiled kernel, developer override of the tile dealing: 0 = as order[G] says, 1 = always spread, 2 = never
+    int32_t spread;            // tiled kernel, tile dealing: 0 = as order[G] says, 1 = always spread, 2 = never
     float* partial;            // [ksplit, partial_rows, N]
     long long partial_rows;
     // EPI_SCATTER
@@ -166,6 +167,16 @@ int wsgemm_chunk_k(int MT);
 // Tiled variant for groups with many rows (ffn_tile.hip); same arguments, ksplit must be 1.
 int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s);
 bool tgemm_supported(int K, int N);   // K a multiple of 32   // k-extent of one LDS chunk = granularity of split-K
+
+// Weights in the fragment order of v_mfma_f32_16x16x32_bf16's second operand (pack.hip).  Element (k, n) of group g
+// goes to  ((((g*KB + k/32)*NG + n/128)*8 + n%8)*64 + (k%32/8)*16 + (n%128)/8)*8 + k%8,  KB = ceil(K/32),
+// NG = ceil(N/128); positions past K or N hold zeros.  A lane's 16 bytes are then 8 consecutive k of one column,
+// a wave's 1 KB is one fragment, and fragment j of a 128-column group holds columns 8c + j (c = lane % 16): a lane's
+// 8 accumulators of a row are 8 consecutive columns.
+inline size_t packed_weight_elems(int G, int K, int N) {
+    return (size_t)G * ((K + 31) / 32) * ((N + 127) / 128) * 4096;
+}
+int launch_pack_weights(const uint16_t* W, uint16_t* packed, int G, int K, int N, hipStream_t s);
 
 // Sums split-K partials in split order, adds the bias and finishes like EPI_STORE (scatter_map ==
 // nullptr) or EPI_SCATTER (scatter_map given; also zero-fills rows of dropped tokens).

@@ -15,9 +15,15 @@ class MoELayer:
     the current stream and returns the output tensor (reused between calls)."""
 
     def __init__(self, T: int, d_model: int, d_ffn: int, E: int, top_k: int, capacity: int, dtype,
-                 Wg, bg, W1, b1, W2, b2, Wd1=None, bd1=None, Wd2=None, bd2=None, export_routing: bool = True):
+                 Wg, bg, W1, b1, W2, b2, Wd1=None, bd1=None, Wd2=None, bd2=None, export_routing: bool = True,
+                 pack_weights: bool = False):
         residual = Wd1 is not None
-        self.shape = B.make_shape(T, d_model, d_ffn, E, top_k, capacity, dtype, residual)
+        if pack_weights:          # one-time re-tiling; the layer then holds the packed copies only
+            W1, W2 = B.moe_pack_weights(W1), B.moe_pack_weights(W2)
+            if residual:
+                Wd1, Wd2 = B.moe_pack_weights(Wd1), B.moe_pack_weights(Wd2)
+        self.shape = B.make_shape(T, d_model, d_ffn, E, top_k, capacity, dtype, residual,
+                                  B.MOE_FLAG_PACKED_WEIGHTS if pack_weights else 0)
         self.weights = (Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2)
         dev = W1.device
         el = torch.float32 if self.shape.dtype == B.MOE_F32 else torch.bfloat16

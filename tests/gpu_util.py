@@ -46,14 +46,14 @@ CANARY_ROWS = 16
 CANARY = 12345.0                            # exactly representable in bf16 and fp32
 
 
-def gpu_forward(inp: LayerInputs, capacity: Optional[int] = None) -> Dict[str, torch.Tensor]:
+def gpu_forward(inp: LayerInputs, capacity: Optional[int] = None, pack: bool = False) -> Dict[str, torch.Tensor]:
     """One moe_layer_forward call.  The output buffer sits between two bands of canary rows, which
     must come back untouched (a write past either end of `out` shows here)."""
     m = amd()
     cfg = inp.cfg
     C = cfg.capacity if capacity is None else capacity
     layer = m.MoELayer(cfg.T, cfg.d_model, cfg.d_ffn, cfg.E, cfg.top_k, C, cfg.dtype, inp.Wg, inp.bg, inp.W1, inp.b1,
-                       inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2)
+                       inp.W2, inp.b2, inp.Wd1, inp.bd1, inp.Wd2, inp.bd2, pack_weights=pack)
     padded = torch.full((cfg.T + 2 * CANARY_ROWS, cfg.d_model), CANARY, dtype=layer.out.dtype, device=layer.out.device)
     layer.out = padded[CANARY_ROWS:CANARY_ROWS + cfg.T]
     out = layer(inp.x)
@@ -102,12 +102,17 @@ def assert_close(gpu_out: torch.Tensor, ref: np.ndarray, dtype: str, what: str =
     return err / scale if scale > 0 else 0.0
 
 
-def check_layer(inp: LayerInputs, capacity: Optional[int] = None, lazy_experts: bool = False) -> Dict[str, float]:
+def check_layer(inp: LayerInputs, capacity: Optional[int] = None, lazy_experts: bool = False,
+                packed_too: Optional[bool] = None) -> Dict[str, float]:
     """Full-layer parity: logits within tolerance of the oracle's own; then the
     oracle evaluates the rest of the layer on the GPU's fp32 logits, routing must
-    match bit for bit and the output within the dtype's tolerance."""
+    match bit for bit and the output within the dtype's tolerance.  bf16 layers
+    run a second time on packed weights (moe_pack_weights) against the same
+    oracle result: the gate does not depend on the weights' layout."""
     cfg = inp.cfg
     C = cfg.capacity if capacity is None else capacity
+    if packed_too is None:
+        packed_too = cfg.dtype == "bf16"
     res = gpu_forward(inp, C)
     h = host(inp, lazy_experts)
     own = orc.gate_logits(h["x"], h["Wg"], h.get("bg"))
@@ -118,12 +123,21 @@ def check_layer(inp: LayerInputs, capacity: Optional[int] = None, lazy_experts: 
                                 Wd1=h.get("Wd1"), bd1=h.get("bd1"), Wd2=h.get("Wd2"), bd2=h.get("bd2"), logits=gl)
     assert_routing_equal(res, ref)
     rel = assert_close(res["out"], ref["out"], cfg.dtype)
+    runs = [res]
+    rel_packed = None
+    if packed_too:
+        resp = gpu_forward(inp, C, pack=True)
+        assert torch.equal(resp["logits"], res["logits"])
+        assert_routing_equal(resp, ref)
+        rel_packed = assert_close(resp["out"], ref["out"], cfg.dtype, "out (packed weights)")
+        runs.append(resp)
     if not cfg.residual:
         dropped = np.all(ref["slot_idx"] < 0, axis=1)
         if dropped.any():
-            go = res["out"].cpu().to(torch.float32).numpy()
-            assert np.all(go[dropped] == 0.0), "fully dropped tokens must be exactly zero"
+            for r in runs:
+                go = r["out"].cpu().to(torch.float32).numpy()
+                assert np.all(go[dropped] == 0.0), "fully dropped tokens must be exactly zero"
     own_route = orc.gate(own, cfg.top_k, C)
     flips = int(np.sum(np.any(own_route["expert_idx"] != ref["expert_idx"], axis=1)))
-    return {"rel_err": rel, "logit_err": lerr, "route_flips_vs_own_logits": flips,
+    return {"rel_err": rel, "rel_err_packed": rel_packed, "logit_err": lerr, "route_flips_vs_own_logits": flips,
             "kept": int(ref["expert_rows"].sum()), "dropped_tokens": int(np.all(ref["slot_idx"] < 0, axis=1).sum())}

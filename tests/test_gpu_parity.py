@@ -167,13 +167,16 @@ def test_dispatch_exact_and_combine(dtype, T, d, E, k, C):
                                                 ("bf16", 1024, 128, 32, 200, True), ("bf16", 1000, 160, 33, 250, True)])
 def test_expert_ffn(dtype, d, f, E, C, bias):
     _check_expert_ffn(dtype, d, f, E, C, bias, None)
+    if dtype == "bf16":
+        _check_expert_ffn(dtype, d, f, E, C, bias, None, pack=True)
 
 
 def test_expert_ffn_unequal_experts():
     """Two full experts among nearly empty ones (and a group count that is not a multiple of 8): the tiled kernel
     deals the column tiles of every expert over the XCDs instead of whole experts."""
-    _check_expert_ffn("bf16", 256, 2048, 9, 300, True, [300, 3, 2, 1, 280, 5, 0, 2, 1])
-    _check_expert_ffn("bf16", 128, 4096, 16, 200, False, [200, 1, 1, 0, 2, 1, 150, 1, 3, 1, 0, 1, 2, 1, 1, 70])
+    for pack in (False, True):
+        _check_expert_ffn("bf16", 256, 2048, 9, 300, True, [300, 3, 2, 1, 280, 5, 0, 2, 1], pack=pack)
+        _check_expert_ffn("bf16", 128, 4096, 16, 200, False, [200, 1, 1, 0, 2, 1, 150, 1, 3, 1, 0, 1, 2, 1, 1, 70], pack=pack)
 
 
 @pytest.mark.parametrize("dtype,d,f,E,C", [("f32", 64, 256, 4, 40), ("bf16", 64, 256, 4, 40), ("bf16", 128, 512, 3, 150)])
@@ -182,9 +185,11 @@ def test_expert_ffn_saturating_gelu(dtype, d, f, E, C):
     z / (1 + exp2(.)), whose exponential overflows to infinity for z << 0 and underflows for z >> 0; the result must
     still be the oracle's (-0 and z)."""
     _check_expert_ffn(dtype, d, f, E, C, True, None, w1_std=1.0, b1_std=5.0)
+    if dtype == "bf16":
+        _check_expert_ffn(dtype, d, f, E, C, True, None, w1_std=1.0, b1_std=5.0, pack=True)
 
 
-def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows, w1_std=0.02, b1_std=0.1):
+def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows, w1_std=0.02, b1_std=0.1, pack=False):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     g = torch.Generator(device=DEV).manual_seed(d + f)
@@ -199,11 +204,14 @@ def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows, w1_std=0.02, b1_std=0
     W2 = (0.02 * torch.randn((E, f, d), generator=g, device=DEV)).to(tdt)
     b1 = (b1_std * torch.randn((E, f), generator=g, device=DEV)).to(tdt) if bias else None
     b2 = (0.1 * torch.randn((E, d), generator=g, device=DEV)).to(tdt) if bias else None
-    shape = m.make_shape(8, d, f, E, 1, C, dtype)
+    shape = m.make_shape(8, d, f, E, 1, C, dtype, flags=m.MOE_FLAG_PACKED_WEIGHTS if pack else 0)
     ws = m.alloc_workspace(shape, DEV)
     canary = 77.0
     ye = torch.full((E, C, d), canary, dtype=tdt, device=DEV)
-    m.moe_expert_ffn(shape, xe, rows, W1, b1, W2, b2, ye, ws)
+    if pack:
+        m.moe_expert_ffn(shape, xe, rows, m.moe_pack_weights(W1), b1, m.moe_pack_weights(W2), b2, ye, ws)
+    else:
+        m.moe_expert_ffn(shape, xe, rows, W1, b1, W2, b2, ye, ws)
     torch.cuda.synchronize()
     f32 = lambda t: None if t is None else t.float().cpu().numpy()
     rows_h = rows.cpu().numpy()

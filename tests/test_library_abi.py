@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_and_status_strings():
     lib = B.load_library()
-    assert B.moe_version() == "0.1"
+    assert B.moe_version() == "0.2"
     assert lib.moe_status_string(0) == b"ok"
     for code in (-1, -2, -3, -4, 99):
         assert len(lib.moe_status_string(code)) > 0
@@ -47,7 +47,7 @@ def test_workspace_bytes():
 
 BAD_SHAPES = [
     (dict(T=0), -1), (dict(E=0), -1), (dict(capacity=0), -1), (dict(top_k=0), -1), (dict(top_k=200), -1),
-    (dict(dtype=5), -1), (dict(residual=2), -1), (dict(flags=1), -1),
+    (dict(dtype=5), -1), (dict(residual=2), -1), (dict(flags=2), -1), (dict(flags=1, dtype=0), -2),
     (dict(top_k=3), -2), (dict(E=2048), -2), (dict(d_model=1028), -2), (dict(d_ffn=4100), -2),
 ]
 
