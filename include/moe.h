@@ -161,6 +161,29 @@ int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expe
                    const void* W1, const void* b1, const void* W2, const void* b2,
                    void* ye /* [E,C,d] */, void* ws, size_t ws_bytes, void* stream);
 
+/* moe_expert_ffn_slice -- one device's share of expert-slicing (Sec. 5.2: when
+ * there are more devices than experts, an expert's parameters are themselves
+ * split across devices, horizontally and vertically as in tensor-slicing).
+ * The slice is a range of the FFN's inner dimension: the caller holds
+ * W1s [E,d,fs] (the slice's columns of W1), b1s [E,fs] or NULL, W2s [E,fs,d]
+ * (the same rows of W2), and shape.d_ffn = fs is the slice's width.  For
+ * c < expert_rows[e]
+ *   ye_partial[e,c,:] = gelu_tanh(xe[e,c,:] W1s[e] + b1s[e]) W2s[e]      (fp32, no b2)
+ * which is the slice's term of the sum over the inner dimension; the slices'
+ * partials add up to the expert output (the all-reduce between the devices of
+ * a sliced expert; on one device: moe_expert_ffn_slice_reduce).  ye_partial is
+ * [E,C,d] float; other rows are left untouched.  bf16 only. */
+int moe_expert_ffn_slice(const moe_shape_t* shape, const void* xe, const int32_t* expert_rows,
+                         const void* W1s, const void* b1s, const void* W2s, float* ye_partial,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* moe_expert_ffn_slice_reduce -- the sum that ends expert-slicing, done locally:
+ *   ye[e,c,:] = b2[e] + sum_s ye_partials[s,e,c,:]     (slices added in index order, fp32)
+ * for c < expert_rows[e]; ye_partials is [n_slices,E,C,d] float, 1 <= n_slices <= 64,
+ * b2 [E,d] or NULL, ye [E,C,d] in shape.dtype.  shape.d_ffn is not used. */
+int moe_expert_ffn_slice_reduce(const moe_shape_t* shape, int32_t n_slices, const float* ye_partials,
+                                const int32_t* expert_rows, const void* b2, void* ye, void* stream);
+
 /* moe_combine -- second layout transform of Sec. 5.4 (replaces the final
  * einsum; scales by the gate probability and restores token order):
  *   out[t,:] = addend[t,:] + sum_j [slot_idx[t,j] >= 0] gate_w[t,j] ye[expert_idx[t,j], slot_idx[t,j], :]

@@ -24,7 +24,7 @@ MOE_FLAG_PACKED_WEIGHTS = 1
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_packed_weights_bytes",
                 "moe_pack_weights", "moe_gate", "moe_gate_noalloc",
                 "moe_gate_noalloc_bytes", "moe_gate_noalloc_max_bytes", "moe_dispatch",
-                "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
+                "moe_expert_ffn", "moe_expert_ffn_slice", "moe_expert_ffn_slice_reduce", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
                 "moe_profile_stride", "moe_profile_calls",
                 "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
 
@@ -75,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_dispatch.argtypes = [sp] + [vp] * 4 + [vp]
     lib.moe_expert_ffn.restype = i32
     lib.moe_expert_ffn.argtypes = [sp] + [vp] * 7 + [vp, st, vp]
+    lib.moe_expert_ffn_slice.restype = i32
+    lib.moe_expert_ffn_slice.argtypes = [sp] + [vp] * 6 + [vp, st, vp]
+    lib.moe_expert_ffn_slice_reduce.restype = i32
+    lib.moe_expert_ffn_slice_reduce.argtypes = [sp, i32] + [vp] * 4 + [vp]
     lib.moe_combine.restype = i32
     lib.moe_combine.argtypes = [sp] + [vp] * 6 + [vp]
     lib.moe_layer_forward.restype = i32
@@ -201,6 +205,22 @@ def moe_expert_ffn(shape, xe, expert_rows, W1, b1, W2, b2, ye, ws) -> None:
         ctypes.byref(shape), _ptr(xe, el), _ptr(expert_rows, torch.int32), _ptr(W1, el), _ptr(b1, el), _ptr(W2, el),
         _ptr(b2, el), _ptr(ye, el), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check("moe_expert_ffn", rc)
+
+
+def moe_expert_ffn_slice(shape, xe, expert_rows, W1s, b1s, W2s, ye_partial, ws) -> None:
+    el = _elem(shape)
+    rc = load_library().moe_expert_ffn_slice(
+        ctypes.byref(shape), _ptr(xe, el), _ptr(expert_rows, torch.int32), _ptr(W1s, el), _ptr(b1s, el), _ptr(W2s, el),
+        _ptr(ye_partial, torch.float32), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check("moe_expert_ffn_slice", rc)
+
+
+def moe_expert_ffn_slice_reduce(shape, n_slices, ye_partials, expert_rows, b2, ye) -> None:
+    el = _elem(shape)
+    rc = load_library().moe_expert_ffn_slice_reduce(
+        ctypes.byref(shape), int(n_slices), _ptr(ye_partials, torch.float32), _ptr(expert_rows, torch.int32), _ptr(b2, el),
+        _ptr(ye, el), _stream())
+    _check("moe_expert_ffn_slice_reduce", rc)
 
 
 def moe_combine(shape, ye, expert_idx, slot_idx, gate_w, addend, out) -> None:

@@ -428,6 +428,50 @@ int moe_expert_ffn(const moe_shape_t* shape, const void* xe, const int32_t* expe
                             at<float>(ws, L.partial), st);
 }
 
+int moe_expert_ffn_slice(const moe_shape_t* shape, const void* xe, const int32_t* expert_rows, const void* W1s,
+                         const void* b1s, const void* W2s, float* ye_partial, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+    if (!xe || !expert_rows || !W1s || !W2s || !ye_partial) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {xe, expert_rows, W1s, b1s, W2s, ye_partial};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    rc = check_ws(shape, ws, ws_bytes);
+    if (rc != MOE_OK) return rc;
+    const WsLayout L = ws_layout(shape);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    FfnPlan plan = plan_ffn(shape);
+    plan.ksplit2 = 1;                                  // the slice itself is the split of the inner dimension
+    int32_t* order = at<int32_t>(ws, L.order);
+    rc = launch_expert_order(expert_rows, shape->E, shape->capacity, order, st);
+    if (rc != MOE_OK) return rc;
+    rc = run_expert_gemm1(shape, plan, xe, nullptr, expert_rows, order, W1s, b1s, at<void>(ws, L.h), st);
+    if (rc != MOE_OK) return rc;
+    WsGemmArgs a{};
+    a.A = at<uint16_t>(ws, L.h); a.B = u16(W2s); a.rows = expert_rows; a.order = order;
+    a.packed = shape->flags & MOE_FLAG_PACKED_WEIGHTS;
+    a.max_rows = shape->capacity; a.G = shape->E; a.K = shape->d_ffn; a.N = shape->d_model;
+    a.a_group_stride = shape->capacity; a.o_group_stride = shape->capacity; a.ksplit = 1;
+    a.partial = ye_partial; a.partial_rows = (long long)shape->E * shape->capacity;
+    return plan.tiled ? launch_tgemm(a, EPI_PARTIAL, st) : launch_wsgemm(a, EPI_PARTIAL, plan.MT, plan.NW2, plan.NBUF, st);
+}
+
+int moe_expert_ffn_slice_reduce(const moe_shape_t* shape, int32_t n_slices, const float* ye_partials,
+                                const int32_t* expert_rows, const void* b2, void* ye, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+    if (n_slices < 1 || n_slices > 64 || !ye_partials || !expert_rows || !ye) return MOE_ERR_INVALID_ARG;
+    if (!aligned16(ye_partials) || !aligned16(expert_rows) || !aligned16(ye) || (b2 && !aligned16(b2)))
+        return MOE_ERR_INVALID_ARG;
+    SplitKReduceArgs r{};
+    r.partial = ye_partials; r.ksplit = n_slices; r.G = shape->E; r.N = shape->d_model; r.group_stride = shape->capacity;
+    r.rows = expert_rows; r.max_rows = shape->capacity; r.bias = u16(b2); r.out = u16(ye); r.top_k = shape->top_k;
+    r.T = shape->T;
+    return launch_splitk_reduce(r, static_cast<hipStream_t>(stream));
+}
+
 int moe_combine(const moe_shape_t* shape, const void* ye, const int32_t* expert_idx, const int32_t* slot_idx,
                 const float* gate_w, const void* addend, void* out, void* stream) {
     int rc = check_shape(shape);

@@ -406,6 +406,7 @@ int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s) {
         case EPI_GELU: return launch_t_epi<EPI_GELU>(a, s);
         case EPI_SCATTER: return launch_t_epi<EPI_SCATTER>(a, s);
         case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, s);
+        case EPI_PARTIAL: return launch_t_epi<EPI_PARTIAL>(a, s);      // ksplit == 1: one fp32 partial, no bias
         default: return MOE_ERR_INVALID_ARG;
     }
 }

@@ -189,6 +189,51 @@ def test_expert_ffn_saturating_gelu(dtype, d, f, E, C):
         _check_expert_ffn(dtype, d, f, E, C, True, None, w1_std=1.0, b1_std=5.0, pack=True)
 
 
+@pytest.mark.parametrize("d,f,E,C,cuts,pack", [(256, 1024, 6, 70, (0, 384, 1024), False), (256, 1024, 6, 70, (0, 512, 1024), True),
+                                               (512, 768, 5, 40, (0, 256, 512, 768), False), (2048, 1024, 9, 3, (0, 640, 1024), True),
+                                               (264, 520, 4, 150, (0, 200, 520), False)])
+def test_expert_ffn_slices_sum_to_the_expert(d, f, E, C, cuts, pack):
+    """Expert-slicing on one device: every slice of the inner dimension gives an fp32 partial output; their sum in
+    slice order plus b2 is the expert FFN of the oracle."""
+    m = U.amd()
+    tdt = torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(d + f + C)
+    rows = torch.randint(0, C + 1, (E,), generator=g, device=DEV).to(torch.int32)
+    rows[0], rows[1] = C, 0
+    xe = torch.randn((E, C, d), generator=g, device=DEV).to(tdt)
+    W1 = (0.02 * torch.randn((E, d, f), generator=g, device=DEV)).to(tdt)
+    W2 = (0.02 * torch.randn((E, f, d), generator=g, device=DEV)).to(tdt)
+    b1 = (0.1 * torch.randn((E, f), generator=g, device=DEV)).to(tdt)
+    b2 = (0.1 * torch.randn((E, d), generator=g, device=DEV)).to(tdt)
+    n = len(cuts) - 1
+    canary = 99.0
+    partials = torch.full((n, E, C, d), canary, dtype=torch.float32, device=DEV)
+    for s_ in range(n):
+        f0, f1 = cuts[s_], cuts[s_ + 1]
+        print(f"slice {s_}: columns {f0}..{f1}", flush=True)
+        shape = m.make_shape(8, d, f1 - f0, E, 1, C, "bf16", flags=m.MOE_FLAG_PACKED_WEIGHTS if pack else 0)
+        ws = m.alloc_workspace(shape, DEV)
+        W1s, W2s = W1[:, :, f0:f1].contiguous(), W2[:, f0:f1, :].contiguous()
+        if pack:
+            W1s, W2s = m.moe_pack_weights(W1s), m.moe_pack_weights(W2s)
+        m.moe_expert_ffn_slice(shape, xe, rows, W1s, b1[:, f0:f1].contiguous(), W2s, partials[s_], ws)
+    shape = m.make_shape(8, d, f, E, 1, C, "bf16")
+    ye = torch.full((E, C, d), 77.0, dtype=tdt, device=DEV)
+    m.moe_expert_ffn_slice_reduce(shape, n, partials, rows, b2, ye)
+    torch.cuda.synchronize()
+    f32 = lambda t: t.float().cpu().numpy()
+    rows_h = rows.cpu().numpy()
+    ref = orc.expert_ffn(f32(xe).astype(np.float64), rows_h, f32(W1), f32(b1), f32(W2), f32(b2))
+    valid = np.arange(C)[None, :] < rows_h[:, None]
+    ye_h, ph = f32(ye), partials.cpu().numpy()
+    assert np.all(ye_h[~valid] == 77.0) and np.all(ph[:, ~valid] == canary)
+    scale = np.max(np.abs(ref[valid]))
+    assert np.max(np.abs(ye_h[valid] - ref[valid])) <= U.TOL["bf16"] * scale
+    # the partials themselves: their fp64 sum plus b2 is the reference before any bf16 rounding of the output
+    total = ph.astype(np.float64).sum(axis=0) + f32(b2).astype(np.float64)[:, None, :]
+    assert np.max(np.abs(total[valid] - ref[valid])) <= U.TOL["bf16"] * scale
+
+
 def _check_expert_ffn(dtype, d, f, E, C, bias, fixed_rows, w1_std=0.02, b1_std=0.1, pack=False):
     m = U.amd()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
