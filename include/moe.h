@@ -207,6 +207,46 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
                       float* gate_w_out, int32_t* expert_rows_out, int32_t* slot_token_out,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* moe_decode_block_forward -- one decode step (one new token per sequence) of a
+ * whole decoder block whose feed-forward part is the MoE layer: the models of
+ * Sec. 3.1 are GPT-like decoders with experts on every other feed-forward layer,
+ * and Sec. 5.4 runs transformer kernels for the non-expert part beside the MoE
+ * kernels.  With T = shape.T sequences, d = d_model, H heads of dh = d/H (64 or
+ * 128), bf16:
+ *   a      = LayerNorm(x; ln1_gamma, ln1_beta)            (eps 1e-5, biased variance)
+ *   q,k,v  = a Wqkv + bqkv                                Wqkv [d,3d], columns q | k | v, head h at h*dh
+ *   o[b,h] = softmax(q[b,h] . K^T / sqrt(dh)) V           K, V = the sequence's pos[b] cached rows + the new one
+ *   x1     = x + o Wo + bo                                Wo [d,d]
+ *   out    = x1 + moe_layer_forward(LayerNorm(x1; ln2_gamma, ln2_beta))
+ * k_cache, v_cache [T,H,max_len,dh]: rows 0..pos[b]-1 of sequence b are read, row
+ * pos[b] is WRITTEN with the new token's key/value (pos[b] is clamped into
+ * 0..max_len-1); the caller advances pos.  LayerNorm parameters are float [d];
+ * biases (bqkv [3d], bo [d]) may be NULL.  The MoE weights are those of
+ * moe_layer_forward (MOE_FLAG_PACKED_WEIGHTS applies to them only); a dense
+ * feed-forward block is E = 1, capacity = T.  Optional exports for parity tests:
+ * x1_out [T,d], moe_in_out [T,d] (the MoE layer's input), logits_out [T,E].
+ * ws >= moe_decode_block_workspace_bytes(shape, block). */
+typedef struct {
+    int32_t n_heads;   /* attention heads; d_model / n_heads must be 64 or 128 */
+    int32_t max_len;   /* positions per sequence in the key/value caches       */
+} moe_block_shape_t;
+
+typedef struct {
+    const float* ln1_gamma; const float* ln1_beta;
+    const void* Wqkv; const void* bqkv;
+    const void* Wo; const void* bo;
+    const float* ln2_gamma; const float* ln2_beta;
+    const float* Wg; const float* bg;
+    const void* W1; const void* b1; const void* W2; const void* b2;
+    const void* Wd1; const void* bd1; const void* Wd2; const void* bd2;
+} moe_block_weights_t;
+
+size_t moe_decode_block_workspace_bytes(const moe_shape_t* shape, const moe_block_shape_t* block);
+int moe_decode_block_forward(const moe_shape_t* shape, const moe_block_shape_t* block, const moe_block_weights_t* weights,
+                             const void* x, void* k_cache, void* v_cache, const int32_t* pos, void* out,
+                             void* x1_out, void* moe_in_out, float* logits_out,
+                             void* ws, size_t ws_bytes, void* stream);
+
 /* Stage timing of moe_layer_forward, for benchmarks (the paper reports the MoE
  * kernels' latency as a whole, Sec. 5.4; this splits it per kernel).
  * moe_profile_enable(n > 0) creates events for the next n calls (the one place

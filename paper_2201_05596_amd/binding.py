@@ -24,7 +24,8 @@ MOE_FLAG_PACKED_WEIGHTS = 1
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_packed_weights_bytes",
                 "moe_pack_weights", "moe_gate", "moe_gate_noalloc",
                 "moe_gate_noalloc_bytes", "moe_gate_noalloc_max_bytes", "moe_dispatch",
-                "moe_expert_ffn", "moe_expert_ffn_slice", "moe_expert_ffn_slice_reduce", "moe_combine", "moe_layer_forward", "moe_profile_enable", "moe_profile_select",
+                "moe_expert_ffn", "moe_expert_ffn_slice", "moe_expert_ffn_slice_reduce", "moe_combine", "moe_layer_forward", "moe_decode_block_workspace_bytes",
+                "moe_decode_block_forward", "moe_profile_enable", "moe_profile_select",
                 "moe_profile_stride", "moe_profile_calls",
                 "moe_profile_stage_count", "moe_profile_stage_name", "moe_profile_elapsed")
 
@@ -32,6 +33,18 @@ ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_
 class MoeShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("T", "d_model", "d_ffn", "E", "top_k", "capacity", "dtype", "residual", "flags")]
+
+
+class MoeBlockShape(ctypes.Structure):
+    _fields_ = [("n_heads", ctypes.c_int32), ("max_len", ctypes.c_int32)]
+
+
+BLOCK_WEIGHT_FIELDS = ("ln1_gamma", "ln1_beta", "Wqkv", "bqkv", "Wo", "bo", "ln2_gamma", "ln2_beta", "Wg", "bg",
+                       "W1", "b1", "W2", "b2", "Wd1", "bd1", "Wd2", "bd2")
+
+
+class MoeBlockWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in BLOCK_WEIGHT_FIELDS]
 
 
 class MoeError(RuntimeError):
@@ -83,6 +96,11 @@ def load_library() -> ctypes.CDLL:
     lib.moe_combine.argtypes = [sp] + [vp] * 6 + [vp]
     lib.moe_layer_forward.restype = i32
     lib.moe_layer_forward.argtypes = [sp] + [vp] * 18 + [vp, st, vp]
+    lib.moe_decode_block_workspace_bytes.restype = st
+    lib.moe_decode_block_workspace_bytes.argtypes = [sp, ctypes.POINTER(MoeBlockShape)]
+    lib.moe_decode_block_forward.restype = i32
+    lib.moe_decode_block_forward.argtypes = [sp, ctypes.POINTER(MoeBlockShape), ctypes.POINTER(MoeBlockWeights)] + \
+        [vp] * 8 + [vp, st, vp]
     lib.moe_profile_enable.restype = i32
     lib.moe_profile_enable.argtypes = [i32]
     lib.moe_profile_select.restype = i32
@@ -241,6 +259,23 @@ def moe_layer_forward(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out,
         _ptr(expert_rows_out, i32), _ptr(slot_token_out, i32),
         _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check("moe_layer_forward", rc)
+
+
+def moe_decode_block_workspace_bytes(shape: MoeShape, block: MoeBlockShape) -> int:
+    return int(load_library().moe_decode_block_workspace_bytes(ctypes.byref(shape), ctypes.byref(block)))
+
+
+def moe_decode_block_forward(shape, block, weights: dict, x, k_cache, v_cache, pos, out, x1_out, moe_in_out, logits_out,
+                             ws) -> None:
+    """`weights`: name -> tensor (or None) for the fields of moe_block_weights_t."""
+    el, f32 = _elem(shape), torch.float32
+    kinds = {"ln1_gamma": f32, "ln1_beta": f32, "ln2_gamma": f32, "ln2_beta": f32, "Wg": f32, "bg": f32}
+    w = MoeBlockWeights(**{n: _ptr(weights.get(n), kinds.get(n, el)) for n in BLOCK_WEIGHT_FIELDS})
+    rc = load_library().moe_decode_block_forward(
+        ctypes.byref(shape), ctypes.byref(block), ctypes.byref(w), _ptr(x, el), _ptr(k_cache, el), _ptr(v_cache, el),
+        _ptr(pos, torch.int32), _ptr(out, el), _ptr(x1_out, el), _ptr(moe_in_out, el), _ptr(logits_out, f32),
+        _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check("moe_decode_block_forward", rc)
 
 
 def moe_profile_enable(max_calls: int) -> None:

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
-SOURCES = ["api.hip", "gate.hip", "gate_bf16.hip", "layout.hip", "pack.hip", "gemm_simple.hip", "ffn_mfma.hip", "ffn_tile.hip"]
+SOURCES = ["api.hip", "gate.hip", "gate_bf16.hip", "layout.hip", "pack.hip", "block.hip", "gemm_simple.hip", "ffn_mfma.hip", "ffn_tile.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

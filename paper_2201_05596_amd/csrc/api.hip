@@ -575,6 +575,125 @@ int moe_layer_forward(const moe_shape_t* shape, const void* x, const float* Wg, 
     return rc;
 }
 
+// ---- one decode step of a whole decoder block ---------------------------------------------------------------------
+namespace {
+
+struct BlockLayout {
+    size_t qkv, attn, proj, x1, xn, moe_out, attn_partial, lin_partial, moe_ws, total;
+};
+constexpr int kLinearMaxSplit = 8;
+
+BlockLayout block_layout(const moe_shape_t* s, const moe_block_shape_t* b) {
+    BlockLayout L{};
+    const size_t T = s->T, d = s->d_model;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+    L.qkv = take(T * 3 * d * 2);
+    L.attn = take(T * d * 2);
+    L.proj = take(T * d * 2);
+    L.x1 = take(T * d * 2);
+    L.xn = take(T * d * 2);
+    L.moe_out = take(T * d * 2);
+    L.attn_partial = take(attn_partial_floats(s->T, b->n_heads, s->d_model / b->n_heads, b->max_len) * 4);
+    L.lin_partial = take((size_t)kLinearMaxSplit * T * 3 * d * 4);
+    L.moe_ws = take(ws_layout(s).total);
+    L.total = off;
+    return L;
+}
+
+int check_block_shape(const moe_shape_t* s, const moe_block_shape_t* b) {
+    const int rc = check_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!b || b->n_heads < 1 || b->max_len < 1) return MOE_ERR_INVALID_ARG;
+    if (s->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+    if (!attn_supported(s->d_model, b->n_heads)) return MOE_ERR_UNSUPPORTED;
+    if ((long long)s->T * b->n_heads >= (1ll << 31) || b->max_len > (1 << 24)) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+// out[T, N] = x[T, K] W[K, N] + bias on the weight-streaming kernel (a decode step has few rows: the product is a
+// read of W); with few output columns the inner dimension is split over more waves and summed in a fixed order
+int run_linear(const uint16_t* x, const uint16_t* W, const uint16_t* bias, uint16_t* out, int T, int K, int N,
+               float* partial, hipStream_t st) {
+    WsGemmArgs a{};
+    a.A = x; a.B = W; a.bias = bias; a.fixed_rows = T; a.max_rows = T; a.G = 1; a.K = K; a.N = N; a.out = out;
+    a.o_group_stride = T; a.a_group_stride = T; a.ksplit = 1;
+    int MT, NW;
+    wsgemm_pick_tile(T, 1, N, &MT, &NW);
+    const long long waves = (long long)((N + 127) / 128) * ((T + MT - 1) / MT);
+    const int chunks = (K + wsgemm_chunk_k(MT) - 1) / wsgemm_chunk_k(MT);
+    long long ks = waves < 1024 ? (2048 + waves - 1) / waves : 1;
+    if (ks > kLinearMaxSplit) ks = kLinearMaxSplit;
+    if (ks > chunks) ks = chunks;
+    if (ks <= 1) return launch_wsgemm(a, EPI_STORE, MT, NW, 2, st);
+    a.ksplit = (int)ks; a.partial = partial; a.partial_rows = T;
+    int rc = launch_wsgemm(a, EPI_PARTIAL, MT, NW, 2, st);
+    if (rc != MOE_OK) return rc;
+    SplitKReduceArgs r{};
+    r.partial = partial; r.ksplit = (int)ks; r.G = 1; r.N = N; r.group_stride = T; r.rows = nullptr; r.max_rows = T;
+    r.bias = bias; r.out = out; r.top_k = 1; r.T = T;
+    return launch_splitk_reduce(r, st);
+}
+
+}  // namespace
+
+size_t moe_decode_block_workspace_bytes(const moe_shape_t* shape, const moe_block_shape_t* block) {
+    if (check_block_shape(shape, block) != MOE_OK) return 0;
+    return block_layout(shape, block).total;
+}
+
+int moe_decode_block_forward(const moe_shape_t* shape, const moe_block_shape_t* block, const moe_block_weights_t* w,
+                             const void* x, void* k_cache, void* v_cache, const int32_t* pos, void* out, void* x1_out,
+                             void* moe_in_out, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_block_shape(shape, block);
+    if (rc != MOE_OK) return rc;
+    if (!w || !x || !k_cache || !v_cache || !pos || !out) return MOE_ERR_INVALID_ARG;
+    if (!w->ln1_gamma || !w->ln1_beta || !w->Wqkv || !w->Wo || !w->ln2_gamma || !w->ln2_beta || !w->Wg || !w->W1 || !w->W2)
+        return MOE_ERR_INVALID_ARG;
+    if (shape->residual && (!w->Wd1 || !w->Wd2)) return MOE_ERR_INVALID_ARG;
+    if (!shape->residual && (w->Wd1 || w->Wd2 || w->bd1 || w->bd2)) return MOE_ERR_INVALID_ARG;
+    const void* ptrs[] = {x, k_cache, v_cache, pos, out, x1_out, moe_in_out, logits_out, w->ln1_gamma, w->ln1_beta, w->Wqkv,
+                          w->bqkv, w->Wo, w->bo, w->ln2_gamma, w->ln2_beta, w->Wg, w->bg, w->W1, w->b1, w->W2, w->b2,
+                          w->Wd1, w->bd1, w->Wd2, w->bd2};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+    const BlockLayout L = block_layout(shape, block);
+    if (!ws || !aligned16(ws) || ws_bytes < L.total) return MOE_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = shape->T, d = shape->d_model, H = block->n_heads, dh = d / H;
+    const float eps = 1e-5f;
+    uint16_t* qkv = at<uint16_t>(ws, L.qkv);
+    uint16_t* attn = at<uint16_t>(ws, L.attn);
+    uint16_t* proj = at<uint16_t>(ws, L.proj);
+    uint16_t* x1 = x1_out ? u16(x1_out) : at<uint16_t>(ws, L.x1);
+    uint16_t* xn = at<uint16_t>(ws, L.xn);
+    uint16_t* moe_in = moe_in_out ? u16(moe_in_out) : xn;
+    uint16_t* moe_out = at<uint16_t>(ws, L.moe_out);
+    float* lin_partial = at<float>(ws, L.lin_partial);
+
+    // a = LayerNorm(x); qkv = a Wqkv + bqkv
+    rc = launch_add_layernorm(u16(x), nullptr, w->ln1_gamma, w->ln1_beta, nullptr, xn, T, d, eps, st);
+    if (rc != MOE_OK) return rc;
+    rc = run_linear(xn, u16(w->Wqkv), u16(w->bqkv), qkv, T, d, 3 * d, lin_partial, st);
+    if (rc != MOE_OK) return rc;
+    // the new token over its sequence's cache (its own key/value rows join the cache)
+    rc = launch_attn_decode(qkv, u16(k_cache), u16(v_cache), pos, at<float>(ws, L.attn_partial), attn, T, H, dh,
+                            block->max_len, st);
+    if (rc != MOE_OK) return rc;
+    rc = run_linear(attn, u16(w->Wo), u16(w->bo), proj, T, d, d, lin_partial, st);
+    if (rc != MOE_OK) return rc;
+    // x1 = x + attention; the MoE layer sees LayerNorm(x1)
+    rc = launch_add_layernorm(u16(x), proj, w->ln2_gamma, w->ln2_beta, x1, moe_in, T, d, eps, st);
+    if (rc != MOE_OK) return rc;
+    rc = layer_forward_checked(shape, moe_in, w->Wg, w->bg, w->W1, w->b1, w->W2, w->b2, w->Wd1, w->bd1, w->Wd2, w->bd2,
+                               moe_out, logits_out, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               at<void>(ws, L.moe_ws), ws_layout(shape).total, stream);
+    g_prof.cur = -1;
+    if (rc != MOE_OK) return rc;
+    return launch_add_rows(x1, moe_out, u16(out), (long long)T * d, st);
+}
+
 int moe_profile_enable(int max_calls) {
     for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
     g_prof.ev.clear(); g_prof.stage.clear(); g_prof.nmarks.clear();

@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const SplitKReduceAr
     }
     for (long long row = wave; row < total_rows; row += nwaves) {
         const int g = (int)(row / a.group_stride), r = (int)(row % a.group_stride);
-        if (r >= min(a.rows[g], a.max_rows)) continue;
+        if (r >= (a.rows ? min(a.rows[g], a.max_rows) : a.max_rows)) continue;
         float gw = 1.f;
         size_t orow = (size_t)row;
         if (a.scatter_map) {

@@ -184,7 +184,7 @@ struct SplitKReduceArgs {
     const float* partial;      // [ksplit, G*group_stride, N]
     int32_t ksplit, G, N;
     long long group_stride;
-    const int32_t* rows;       // [G]
+    const int32_t* rows;       // [G], or nullptr: max_rows for every group
     int32_t max_rows;
     const uint16_t* bias;      // [G, N] or nullptr
     uint16_t* out;
@@ -195,5 +195,14 @@ struct SplitKReduceArgs {
     int32_t T;
 };
 int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s);
+
+// ---- the non-expert half of a decoder block, one decode step (block.hip) --------------------------------------
+int launch_add_layernorm(const uint16_t* x, const uint16_t* r /* or nullptr */, const float* gamma, const float* beta,
+                         uint16_t* sum_out /* x + r, or nullptr */, uint16_t* y, int T, int d, float eps, hipStream_t s);
+int launch_add_rows(const uint16_t* a, const uint16_t* b, uint16_t* out, long long n, hipStream_t s);
+bool attn_supported(int d, int H);
+size_t attn_partial_floats(int T, int H, int dh, int Lmax);
+int launch_attn_decode(const uint16_t* qkv, uint16_t* cache_k, uint16_t* cache_v, const int32_t* pos, float* partial,
+                       uint16_t* attn, int T, int H, int dh, int Lmax, hipStream_t s);
 
 }  // namespace moe

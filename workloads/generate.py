@@ -91,6 +91,56 @@ def make_inputs(cfg: MoEConfig, device: str = "cpu", bias_std: float = 0.0) -> L
     return LayerInputs(cfg, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2)
 
 
+@dataclass
+class BlockInputs:
+    """One decode step of a decoder block: the MoE layer's inputs plus the attention half's."""
+    layer: LayerInputs                   # x [T, d] is the block's input; the MoE weights
+    n_heads: int
+    max_len: int
+    ln1_gamma: torch.Tensor              # [d] f32
+    ln1_beta: torch.Tensor
+    ln2_gamma: torch.Tensor
+    ln2_beta: torch.Tensor
+    Wqkv: torch.Tensor                   # [d, 3d]
+    bqkv: torch.Tensor                   # [3d]
+    Wo: torch.Tensor                     # [d, d]
+    bo: torch.Tensor                     # [d]
+    k_cache: torch.Tensor                # [T, H, max_len, dh]
+    v_cache: torch.Tensor
+    pos: torch.Tensor                    # [T] int32: cached positions per sequence
+
+
+def make_block_inputs(cfg: MoEConfig, n_heads: int, max_len: int, device: str = "cpu", bias_std: float = 0.02,
+                      pos_mode: str = "mixed") -> BlockInputs:
+    """Attention-half tensors around make_inputs(cfg): LayerNorm gains ~ N(1, 0.1^2), shifts ~ N(0, 0.1^2);
+    projection weights ~ N(0, 0.02^2) (Wqkv scaled up so that attention is not uniform); caches ~ N(0,1);
+    pos: "mixed" = uniform over 0..max_len-1 with the two extremes forced in, "full" = max_len-1 everywhere."""
+    layer = make_inputs(cfg, device, bias_std=bias_std)
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed + 1000)
+    T, d = cfg.T, cfg.d_model
+    dh = d // n_heads
+    wdt = torch.bfloat16
+    f32 = torch.float32
+    ln = lambda mean: (mean + 0.1 * torch.randn((d,), generator=gen, device=dev, dtype=f32))
+    ln1_gamma, ln1_beta, ln2_gamma, ln2_beta = ln(1.0), ln(0.0), ln(1.0), ln(0.0)
+    Wqkv = _normal((d, 3 * d), 4 * _WEIGHT_STD, wdt, dev, gen)
+    Wo = _normal((d, d), _WEIGHT_STD, wdt, dev, gen)
+    bqkv = _normal((3 * d,), bias_std, wdt, dev, gen) if bias_std > 0 else torch.zeros((3 * d,), dtype=wdt, device=dev)
+    bo = _normal((d,), bias_std, wdt, dev, gen) if bias_std > 0 else torch.zeros((d,), dtype=wdt, device=dev)
+    k_cache = _normal((T, n_heads, max_len, dh), 1.0, wdt, dev, gen)
+    v_cache = _normal((T, n_heads, max_len, dh), 1.0, wdt, dev, gen)
+    if pos_mode == "full":
+        pos = torch.full((T,), max_len - 1, dtype=torch.int32, device=dev)
+    else:
+        pos = torch.randint(0, max_len, (T,), generator=gen, device=dev).to(torch.int32)
+        pos[0] = 0
+        pos[-1] = max_len - 1
+    return BlockInputs(layer, n_heads, max_len, ln1_gamma, ln1_beta, ln2_gamma, ln2_beta, Wqkv, bqkv, Wo, bo, k_cache,
+                       v_cache, pos)
+
+
 def make_logits(T: int, E: int, seed: int, kind: str = "normal", device: str = "cpu") -> torch.Tensor:
     """fp32 gate logits for routing-only tests.
 
