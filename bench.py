@@ -153,6 +153,47 @@ def time_config(cfg, steps, warmup, pack):
     return rec, inp, rows
 
 
+def time_decode_block(steps, warmup, pack):
+    """One decode step of a whole decoder block at the decode workload's shape (c4: 64 sequences, hidden 2048,
+    16 heads, 128 experts) with a full 2048-token key/value cache: extra record, not the headline metric."""
+    import torch
+    import paper_2201_05596_amd as moe
+    from workloads import CONFIGS, make_block_inputs
+
+    cfg, heads, max_len = CONFIGS["c4"], 16, 2048
+    bi = make_block_inputs(cfg, heads, max_len, "cuda:0", bias_std=0.0, pos_mode="full")
+    lay = bi.layer
+    T, d, f, E = cfg.T, cfg.d_model, cfg.d_ffn, cfg.E
+    shape = moe.make_shape(T, d, f, E, cfg.top_k, cfg.capacity, "bf16", flags=moe.MOE_FLAG_PACKED_WEIGHTS if pack else 0)
+    block = moe.MoeBlockShape(heads, max_len)
+    ws = torch.empty(moe.moe_decode_block_workspace_bytes(shape, block), dtype=torch.uint8, device="cuda:0")
+    pk = moe.moe_pack_weights if pack else (lambda w: w)
+    weights = dict(ln1_gamma=bi.ln1_gamma, ln1_beta=bi.ln1_beta, Wqkv=bi.Wqkv, bqkv=bi.bqkv, Wo=bi.Wo, bo=bi.bo,
+                   ln2_gamma=bi.ln2_gamma, ln2_beta=bi.ln2_beta, Wg=lay.Wg, bg=lay.bg, W1=pk(lay.W1), b1=lay.b1,
+                   W2=pk(lay.W2), b2=lay.b2)
+    out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda:0")
+    logits = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        moe.moe_decode_block_forward(shape, block, weights, lay.x, bi.k_cache, bi.v_cache, bi.pos, out, None, None, logits, ws)
+
+    for _ in range(RAMP_STEPS + warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / steps
+    touched = int(torch.unique(logits.argmax(dim=1)).numel())          # top-1: experts that win at least one token
+    cache_bytes = 2 * T * heads * max_len * (d // heads) * 2
+    bytes_alg = cache_bytes + (4 * d * d + 4 * d) * 2 + touched * (2 * d * f + f + d) * 2 + 2 * T * d * 2 + d * E * 4
+    return {"workload": f"decode block: {describe(cfg)}, {heads} heads, key/value cache of {max_len} positions, all full",
+            "us_per_block": us, "tokens_per_s": T / (us * 1e-6), "steps": steps, "algorithmic_bytes": bytes_alg,
+            "kv_cache_bytes": cache_bytes, "touched_experts": touched, "hbm_GBps": bytes_alg / (us * 1e-6) / 1e9,
+            "hbm_frac": bytes_alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+
 def cpu_baseline(inp, cfg, rows, budget_s=12.0):
     """The oracle as it stands on the host cores, on a bounded sample of the workload: the gate, the dispatch and
     the combine on all tokens, the expert FFNs on every n-th touched expert (by row count, busiest first) until the
@@ -240,6 +281,10 @@ def main() -> int:
             configs[name] = rec
             del inp
             torch.cuda.empty_cache()
+        extras = {"decode_block_c4": time_decode_block(SUB_STEPS, args.warmup, not args.plain_weights)}
+        torch.cuda.empty_cache()
+    else:
+        extras = {}
     head, inp, rows = time_config(head_cfg, args.steps, args.warmup, not args.plain_weights)
     configs[head_cfg.name] = head
 
@@ -264,6 +309,7 @@ def main() -> int:
         "layer_roofline": head["layer_roofline"],
         "stage_ms": head["stage_ms"],
         "configs": {n: configs[n] for n in ALL_CONFIGS if n in configs} if not args.only else {},
+        "extras": extras,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, head_cfg, rows)

@@ -55,7 +55,10 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
 enum {
     /* W1, W2 (and Wd1, Wd2) are not the plain [E,d,f] / [E,f,d] arrays but the
      * buffers moe_pack_weights() wrote from them (bf16 only). */
-    MOE_FLAG_PACKED_WEIGHTS = 1
+    MOE_FLAG_PACKED_WEIGHTS = 1,
+    /* Wg is not the plain float [d,E] array but the buffer moe_pack_gate() wrote
+     * from it (bf16 tokens, d_model a multiple of 32, at most 128 experts). */
+    MOE_FLAG_PACKED_GATE = 2
 };
 
 /* Shape of one MoE layer.  Limits: T >= 1, 1 <= E <= 1024, top_k in {1,2} and
@@ -97,6 +100,17 @@ const char* moe_version(void);
  * multiples of 8.  moe_packed_weights_bytes returns 0 for sizes it rejects. */
 size_t moe_packed_weights_bytes(int32_t G, int32_t K, int32_t N);
 int moe_pack_weights(int32_t G, int32_t K, int32_t N, const void* W, void* packed, void* stream);
+
+/* moe_pack_gate -- optional one-time preparation of the gate weights for bf16
+ * layers: every fp32 weight as the exact sum of three bf16 numbers, laid out as
+ * matrix-instruction operands (the gate kernel otherwise does this split into
+ * its workspace at every call, one kernel launch more; Sec. 5.4 counts kernel
+ * launches among the gate's costs).  `packed` receives moe_packed_gate_bytes(d,E)
+ * bytes (0 = shape not covered: d_model not a multiple of 32, or E > 128); pass it
+ * as Wg (cast to const float*) with MOE_FLAG_PACKED_GATE.  Logits are bit-identical
+ * to those from the plain weights. */
+size_t moe_packed_gate_bytes(int32_t d_model, int32_t E);
+int moe_pack_gate(int32_t d_model, int32_t E, const float* Wg, void* packed, void* stream);
 
 /* moe_gate -- the fused gating function of Sec. 5.4: gate logits, softmax,
  * top-k, the cumulative sum that gives each token its position inside its

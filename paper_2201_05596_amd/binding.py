@@ -21,8 +21,9 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK = 0
 MOE_FLAG_PACKED_WEIGHTS = 1
+MOE_FLAG_PACKED_GATE = 2
 ENTRY_POINTS = ("moe_workspace_bytes", "moe_status_string", "moe_version", "moe_packed_weights_bytes",
-                "moe_pack_weights", "moe_gate", "moe_gate_noalloc",
+                "moe_pack_weights", "moe_packed_gate_bytes", "moe_pack_gate", "moe_gate", "moe_gate_noalloc",
                 "moe_gate_noalloc_bytes", "moe_gate_noalloc_max_bytes", "moe_dispatch",
                 "moe_expert_ffn", "moe_expert_ffn_slice", "moe_expert_ffn_slice_reduce", "moe_combine", "moe_layer_forward", "moe_decode_block_workspace_bytes",
                 "moe_decode_block_forward", "moe_profile_enable", "moe_profile_select",
@@ -76,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_packed_weights_bytes.argtypes = [i32, i32, i32]
     lib.moe_pack_weights.restype = i32
     lib.moe_pack_weights.argtypes = [i32, i32, i32, vp, vp, vp]
+    lib.moe_packed_gate_bytes.restype = st
+    lib.moe_packed_gate_bytes.argtypes = [i32, i32]
+    lib.moe_pack_gate.restype = i32
+    lib.moe_pack_gate.argtypes = [i32, i32, vp, vp, vp]
     lib.moe_gate.restype = i32
     lib.moe_gate.argtypes = [sp] + [vp] * 9 + [vp, st, vp]
     lib.moe_gate_noalloc.restype = i32
@@ -181,6 +186,22 @@ def moe_pack_weights(W: torch.Tensor) -> torch.Tensor:
         raise MoeError("moe_packed_weights_bytes", -2, "unsupported size")
     packed = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=W.device)
     _check("moe_pack_weights", load_library().moe_pack_weights(G, K, N, _ptr(W, torch.bfloat16), _ptr(packed), _stream()))
+    return packed
+
+
+def moe_packed_gate_bytes(d_model: int, E: int) -> int:
+    return int(load_library().moe_packed_gate_bytes(int(d_model), int(E)))
+
+
+def moe_pack_gate(Wg: torch.Tensor) -> Optional[torch.Tensor]:
+    """Packed copy of the float gate weights [d,E] for MOE_FLAG_PACKED_GATE, or None when the shape is not covered.
+    The buffer is typed float32 only so that it passes where Wg is expected; its contents are bf16 triples."""
+    d, E = Wg.shape
+    nbytes = moe_packed_gate_bytes(d, E)
+    if nbytes == 0:
+        return None
+    packed = torch.empty((nbytes + 3) // 4, dtype=torch.float32, device=Wg.device)
+    _check("moe_pack_gate", load_library().moe_pack_gate(d, E, _ptr(Wg, torch.float32), _ptr(packed), _stream()))
     return packed
 
 

@@ -64,8 +64,10 @@ int check_shape(const moe_shape_t* s) {
     if (s->top_k < 1 || s->top_k > s->E) return MOE_ERR_INVALID_ARG;
     if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
     if (s->residual != 0 && s->residual != 1) return MOE_ERR_INVALID_ARG;
-    if (s->flags & ~MOE_FLAG_PACKED_WEIGHTS) return MOE_ERR_INVALID_ARG;
+    if (s->flags & ~(MOE_FLAG_PACKED_WEIGHTS | MOE_FLAG_PACKED_GATE)) return MOE_ERR_INVALID_ARG;
     if ((s->flags & MOE_FLAG_PACKED_WEIGHTS) && s->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+    if ((s->flags & MOE_FLAG_PACKED_GATE) && (s->dtype != MOE_BF16 || !gate_bf16_supported(s->d_model, s->E)))
+        return MOE_ERR_UNSUPPORTED;
     if (s->top_k > 2 || s->E > 1024) return MOE_ERR_UNSUPPORTED;
     const int mult = s->dtype == MOE_F32 ? 4 : 8;
     if (s->d_model % mult || s->d_ffn % mult) return MOE_ERR_UNSUPPORTED;
@@ -168,11 +170,14 @@ int static_scratch(void** out) {
     return MOE_OK;
 }
 
-// gate logits: bf16 tokens go to the bf16 matrix cores when the shape allows, everything else to the fp32 ones
+// gate logits: bf16 tokens go to the bf16 matrix cores when the shape allows, everything else to the fp32 ones.
+// With MOE_FLAG_PACKED_GATE, Wg is the buffer moe_pack_gate wrote and no weight is split at call time.
 int run_gate_logits(const moe_shape_t* s, const void* x, const float* Wg, const float* bg, float* logits, void* ws,
                     const WsLayout& L, hipStream_t st) {
+    const bool packed = s->flags & MOE_FLAG_PACKED_GATE;
     if (s->dtype == MOE_BF16 && gate_bf16_supported(s->d_model, s->E))
-        return launch_gate_logits_bf16(x, Wg, bg, logits, s->T, s->d_model, s->E, at<void>(ws, L.wg_frags), st);
+        return launch_gate_logits_bf16(x, packed ? nullptr : Wg, packed ? Wg : nullptr, bg, logits, s->T, s->d_model, s->E,
+                                       at<void>(ws, L.wg_frags), st);
     return launch_gate_logits(x, s->dtype, Wg, bg, logits, s->T, s->d_model, s->E, st);
 }
 
@@ -185,15 +190,16 @@ int run_gate(const moe_shape_t* s, const void* x, const float* Wg, const float* 
     int rc;
     if (s->dtype == MOE_BF16 && gate_bf16_fused_supported(s->T, s->d_model, s->E)) {
         int tb = 0;
-        const int32_t *hist = nullptr, *coarse = nullptr;
+        const int32_t* hist = nullptr;
+        const bool packed = s->flags & MOE_FLAG_PACKED_GATE;
         if (profile) prof_pre(ST_LOGITS, st);
-        rc = launch_gate_bf16_fused(x, Wg, bg, logits, s->T, s->d_model, s->E, s->top_k, expert_idx, slot_idx, gate_w,
-                                    at<void>(ws, L.wg_frags), scratch, &tb, &hist, &coarse, st);
+        rc = launch_gate_bf16_fused(x, packed ? nullptr : Wg, packed ? Wg : nullptr, bg, logits, s->T, s->d_model, s->E,
+                                    s->top_k, expert_idx, slot_idx, gate_w, at<void>(ws, L.wg_frags), scratch, &tb, &hist, st);
         if (profile) prof_mark(ST_LOGITS, st);
         if (rc != MOE_OK) return rc;
         if (profile) prof_pre(ST_ROUTE, st);
         rc = launch_route_finalize(s->T, s->E, s->top_k, s->capacity, tb, expert_idx, slot_idx, rows, slot_token, order,
-                                   hist, coarse, st);
+                                   hist, st);
         if (profile) prof_mark(ST_ROUTE, st);
         return rc;
     }
@@ -327,6 +333,16 @@ const char* moe_version(void) { return "0.2"; }
 size_t moe_packed_weights_bytes(int32_t G, int32_t K, int32_t N) {
     if (G < 1 || K < 8 || N < 8 || K % 8 || N % 8) return 0;
     return packed_weight_elems(G, K, N) * 2;
+}
+
+size_t moe_packed_gate_bytes(int32_t d_model, int32_t E) {
+    if (d_model < 1 || E < 1) return 0;
+    return gate_bf16_ws_bytes(d_model, E);            // 0 for shapes the bf16 gate kernel does not cover
+}
+
+int moe_pack_gate(int32_t d_model, int32_t E, const float* Wg, void* packed, void* stream) {
+    if (d_model < 1 || E < 1 || !Wg || !packed || !aligned16(Wg) || !aligned16(packed)) return MOE_ERR_INVALID_ARG;
+    return launch_pack_gate(Wg, packed, d_model, E, static_cast<hipStream_t>(stream));
 }
 
 int moe_pack_weights(int32_t G, int32_t K, int32_t N, const void* W, void* packed, void* stream) {

@@ -456,14 +456,14 @@ int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order
 
 constexpr int kMaxFine = 8;      // fine blocks per 256 tokens at most (32-token tiles)
 
-// hist holds one histogram [K][E] per block of TB tokens (TB divides 256, TB >= 32), coarse one per 256 tokens
-// (the sum of its 256/TB fine ones; the same array when TB is 256).  A work-group finalises 256 tokens.
+// hist holds one histogram [K][E] per block of TB tokens (TB divides 256, TB >= 32).  A work-group finalises 256
+// tokens.  Every work-group sums the histograms of all blocks before its own: the reads grow with the square of the
+// number of blocks (T = 16384, E = 64, top-2: 8 MB in all, served by L2), a stated limit of this kernel.
 template <int K>
 __device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E, int C, int nblocks, int TB,
                                                     const int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot_idx,
                                                     int32_t* __restrict__ expert_rows, int32_t* __restrict__ slot_token,
-                                                    int32_t* __restrict__ expert_order, const int32_t* __restrict__ hist,
-                                                    const int32_t* __restrict__ coarse) {
+                                                    int32_t* __restrict__ expert_order, const int32_t* __restrict__ hist) {
     const int ncol = K * E;                                // column = (choice j, expert e)
     const int q = kRouteTokens / TB;                       // fine blocks per work-group
     int32_t* base = smem;                                  // [q][K][E] rows before the fine block's tokens
@@ -472,17 +472,19 @@ __device__ __forceinline__ void route_finalize_body(int32_t* smem, int T, int E,
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
 
-    // the coarse histograms are summed with all 256 threads: R row groups each take every R-th block,
+    // the blocks' histograms are summed with all 256 threads: R row groups each take every R-th block,
     // partial sums meet in LDS
     const int R = ncol >= kRouteTokens ? 1 : kRouteTokens / ncol;
     for (int idx = tid; idx < R * ncol; idx += kRouteTokens) {
         const int col = idx % ncol, rg = idx / ncol;
         int pre = 0, tot = 0;
-#pragma unroll 8
-        for (int bb = rg; bb < nblocks; bb += R) {
-            const int v = coarse[(size_t)bb * ncol + col];
+        // every TB-token block's histogram once; those of 256-token blocks before this one also count as "before me"
+        const int nfine = (T + TB - 1) / TB, first_own = b * q;
+#pragma unroll 16
+        for (int fb = rg; fb < nfine; fb += R) {
+            const int v = hist[(size_t)fb * ncol + col];
             tot += v;
-            pre += bb < b ? v : 0;
+            pre += fb < first_own ? v : 0;
         }
         part[rg * ncol + col] = pre;
         part[(R + rg) * ncol + col] = tot;
@@ -567,11 +569,9 @@ __global__ __launch_bounds__(kRouteTokens) void route_finalize_kernel(int T, int
                                                                       int32_t* __restrict__ expert_rows,
                                                                       int32_t* __restrict__ slot_token,
                                                                       int32_t* __restrict__ expert_order,
-                                                                      const int32_t* __restrict__ hist,
-                                                                      const int32_t* __restrict__ coarse) {
+                                                                      const int32_t* __restrict__ hist) {
     extern __shared__ int32_t smem[];
-    route_finalize_body<K>(smem, T, E, C, nblocks, TB, expert_idx, slot_idx, expert_rows, slot_token, expert_order, hist,
-                           coarse);
+    route_finalize_body<K>(smem, T, E, C, nblocks, TB, expert_idx, slot_idx, expert_rows, slot_token, expert_order, hist);
 }
 
 // At most 256 tokens (decode): one block, whose local ranks are already global ones -- the whole routing in one
@@ -623,23 +623,23 @@ size_t route_finalize_lds_bytes(int E, int k, int TB) {
 
 int launch_route_finalize(int T, int E, int k, int C, int TB, const int32_t* expert_idx, int32_t* slot_idx,
                           int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order, const int32_t* hist,
-                          const int32_t* coarse, hipStream_t s) {
+                          hipStream_t s) {
     const int nb = (T + kRouteTokens - 1) / kRouteTokens;
     const size_t sm = route_finalize_lds_bytes(E, k, TB);
     const int grid = nb + (expert_order ? 1 : 0);               // + the block that ranks the experts
     if (k == 1)
         hipLaunchKernelGGL((route_finalize_kernel<1>), dim3(grid), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
-                           slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
+                           slot_idx, expert_rows, slot_token, expert_order, hist);
     else
         hipLaunchKernelGGL((route_finalize_kernel<2>), dim3(grid), dim3(kRouteTokens), sm, s, T, E, C, nb, TB, expert_idx,
-                           slot_idx, expert_rows, slot_token, expert_order, hist, coarse);
+                           slot_idx, expert_rows, slot_token, expert_order, hist);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-// fine histograms for blocks of 32 tokens at the finest, plus the coarse ones
+// histograms for blocks of 32 tokens at the finest
 size_t route_scratch_ints(int T, int E, int k) {
-    const size_t fine = ((size_t)T + 31) / 32, coarse = ((size_t)T + kRouteTokens - 1) / kRouteTokens;
-    return (fine + coarse) * (size_t)k * (size_t)E;
+    const size_t fine = ((size_t)T + 31) / 32;
+    return fine * (size_t)k * (size_t)E;
 }
 
 int launch_route(const float* logits, int T, int E, int k, int C, int32_t* expert_idx, int32_t* slot_idx,
@@ -687,9 +687,9 @@ int launch_route(const float* logits, int T, int E, int k, int C, int32_t* exper
     }
 #undef MOE_ROUTE_LOCAL
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    // the block histograms are per 256 tokens: fine and coarse coincide
+    // the block histograms are per 256 tokens
     return launch_route_finalize(T, E, k, C, kRouteTokens, expert_idx, slot_idx, expert_rows, slot_token, expert_order,
-                                 scratch, scratch, s);
+                                 scratch, s);
 }
 
 }  // namespace moe

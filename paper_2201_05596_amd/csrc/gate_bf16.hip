@@ -12,8 +12,8 @@
 //
 // Kernels:
 //   * gate_prepare_kernel writes the three pieces as ready-made MFMA B fragments (1 KB each: lane l
-//     holds k = 8*(l/16)..+7 of expert column l%16), ordered [k-block][expert tile][piece], and clears
-//     the coarse routing histograms;
+//     holds k = 8*(l/16)..+7 of expert column l%16), ordered [k-block][expert tile][piece]: into the
+//     workspace at every call, or once into a buffer the caller keeps (packed gate weights);
 //   * gate_bf16_kernel: a work-group owns a tile of 16*MA tokens x 16*NE experts; its four waves
 //     split the k-blocks (wave w takes blocks w, w+4, ...) and each computes the whole tile for its
 //     blocks, so no operand byte is fetched twice by a work-group.  Every operand fragment is one
@@ -22,9 +22,8 @@
 //     order, the finished tile is laid out [token][expert] in LDS and written with 16-byte stores.
 //     When the tile spans all experts (K = 1 or 2) the kernel goes on to the first half of the
 //     routing on the tile it holds: top-k and gate weights per token (16 lanes per token), the rank of
-//     each token among the tile's tokens with the same expert (ballots), the tile's histogram, and its
-//     sum into the histogram of the enclosing block of 256 tokens (integer atomics: the result does not
-//     depend on their order).  route_finalize_kernel turns ranks into rows.
+//     each token among the tile's tokens with the same expert (ballots) and the tile's histogram.
+//     route_finalize_kernel turns ranks into rows.
 //     With few tokens the experts are split over work-groups instead (K = 0: logits only) so that
 //     more CUs take part, and the routing runs as a kernel of its own.
 // Requires d_model to be a multiple of 32 and at most 128 experts; other shapes use the fp32 kernel.
@@ -40,11 +39,10 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kKB = 32;                  // k per MFMA
 constexpr int kFragElems = 512;          // bf16 elements of one fragment (64 lanes x 8)
-// KB k-blocks x ET expert tiles x 3 pieces; one thread per (k-block, expert tile, lane).  Also clears `zero`.
+// KB k-blocks x ET expert tiles x 3 pieces; one thread per (k-block, expert tile, lane).
 __global__ __launch_bounds__(256) void gate_prepare_kernel(const float* __restrict__ Wg, uint16_t* __restrict__ frags, int d,
-                                                           int E, int KB, int ET, int32_t* __restrict__ zero, int nzero) {
+                                                           int E, int KB, int ET) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    for (long long i = idx; i < nzero; i += (long long)gridDim.x * 256) zero[i] = 0;
     if (idx >= (long long)KB * ET * 64) return;
     const int lane = (int)(idx & 63);
     const long long fe = idx >> 6;
@@ -96,7 +94,7 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
                                                         const float* __restrict__ bg, float* __restrict__ logits, int T, int d,
                                                         int E, int ET, int32_t* __restrict__ expert_idx,
                                                         int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
-                                                        int32_t* __restrict__ hist, int32_t* __restrict__ coarse) {
+                                                        int32_t* __restrict__ hist) {
     typedef GateLds<MA, NE, K> L;
     constexpr int D = GateCfg<MA, NE>::D, PER = GateCfg<MA, NE>::PER, WK = 4, TM = L::TM, TN = L::TN, STRIDE = L::STRIDE;
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -287,20 +285,17 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
             }
         }
         __syncthreads();
-        // histogram [K][E] of this tile, and its share of the enclosing 256-token block's
-        constexpr int FINE_PER_COARSE = kRouteTokens / TM;
+        // histogram [K][E] of this tile
         for (int i = tid; i < KK * E; i += 256) {
             const int j = i / E, e = i % E;
-            const int c = h_sh[j * TN + e];
-            hist[(size_t)blockIdx.x * KK * E + i] = c;
-            if (c) atomicAdd(&coarse[(size_t)(blockIdx.x / FINE_PER_COARSE) * KK * E + i], c);
+            hist[(size_t)blockIdx.x * KK * E + i] = h_sh[j * TN + e];
         }
     }
 }
 
 template <int MA, int NE, int K>
 int launch_cfg(const uint16_t* x, const uint16_t* frags, const float* bg, float* logits, int T, int d, int E, int ET,
-               int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* hist, int32_t* coarse, hipStream_t s) {
+               int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* hist, hipStream_t s) {
     constexpr int smem = GateLds<MA, NE, K>::BYTES;
     static bool attr_set = false;             // one flag per instantiation
     if (!attr_set) {
@@ -311,7 +306,7 @@ int launch_cfg(const uint16_t* x, const uint16_t* frags, const float* bg, float*
     }
     const dim3 grid((T + 16 * MA - 1) / (16 * MA), ET / NE);
     hipLaunchKernelGGL((gate_bf16_kernel<MA, NE, K>), grid, dim3(256), smem, s, x, frags, bg, logits, T, d, E, ET, expert_idx,
-                       slot_idx, gate_w, hist, coarse);
+                       slot_idx, gate_w, hist);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -330,21 +325,28 @@ size_t gate_bf16_ws_bytes(int d, int E) {
     return (size_t)(d / kKB) * padded_expert_tiles(E) * 3 * kFragElems * sizeof(uint16_t);
 }
 
-static int launch_prepare(const float* Wg, uint16_t* frags, int d, int E, int KB, int ET, int32_t* zero, int nzero,
-                          hipStream_t s) {
+static int launch_prepare(const float* Wg, uint16_t* frags, int d, int E, int KB, int ET, hipStream_t s) {
     const long long threads = (long long)KB * ET * 64;
-    hipLaunchKernelGGL(gate_prepare_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, Wg, frags, d, E, KB, ET,
-                       zero, nzero);
+    hipLaunchKernelGGL(gate_prepare_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, Wg, frags, d, E, KB, ET);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
-                            void* frag_ws, hipStream_t s) {
-    if (!gate_bf16_supported(d, E) || !frag_ws) return MOE_ERR_INVALID_ARG;
+int launch_pack_gate(const float* Wg, void* packed, int d, int E, hipStream_t s) {
+    if (!gate_bf16_supported(d, E)) return MOE_ERR_UNSUPPORTED;
+    return launch_prepare(Wg, static_cast<uint16_t*>(packed), d, E, d / kKB, padded_expert_tiles(E), s);
+}
+
+// Wg_packed != nullptr: the gate weights as launch_pack_gate wrote them (Wg and frag_ws are then not used)
+int launch_gate_logits_bf16(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T,
+                            int d, int E, void* frag_ws, hipStream_t s) {
+    if (!gate_bf16_supported(d, E) || (!frag_ws && !Wg_packed)) return MOE_ERR_INVALID_ARG;
     const int KB = d / kKB, ET = padded_expert_tiles(E);
-    uint16_t* frags = static_cast<uint16_t*>(frag_ws);
-    const int rc = launch_prepare(Wg, frags, d, E, KB, ET, nullptr, 0, s);
-    if (rc != MOE_OK) return rc;
+    const uint16_t* frags = static_cast<const uint16_t*>(Wg_packed);
+    if (!frags) {
+        const int rc = launch_prepare(Wg, static_cast<uint16_t*>(frag_ws), d, E, KB, ET, s);
+        if (rc != MOE_OK) return rc;
+        frags = static_cast<const uint16_t*>(frag_ws);
+    }
     const uint16_t* xb = static_cast<const uint16_t*>(x);
     // Largest tile (fewest operand bytes per output) that still gives every CU a work-group; when even
     // the smallest tile cannot (few tokens), the smallest one: most work-groups, least time per CU.
@@ -355,7 +357,7 @@ int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, flo
             if ((long long)((T + 16 * ma - 1) / (16 * ma)) * (ET / ne) >= 256) { MA = ma; NE = ne; found = true; }
 #define MOE_GATE_CASE(ma, ne) \
     if (MA == ma && NE == ne)   \
-    return launch_cfg<ma, ne, 0>(xb, frags, bg, logits, T, d, E, ET, nullptr, nullptr, nullptr, nullptr, nullptr, s)
+    return launch_cfg<ma, ne, 0>(xb, frags, bg, logits, T, d, E, ET, nullptr, nullptr, nullptr, nullptr, s)
     MOE_GATE_CASE(4, 4); MOE_GATE_CASE(4, 2); MOE_GATE_CASE(4, 1);
     MOE_GATE_CASE(2, 4); MOE_GATE_CASE(2, 2); MOE_GATE_CASE(2, 1);
 #undef MOE_GATE_CASE
@@ -366,25 +368,28 @@ int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, flo
 // routing kernel is faster then.
 bool gate_bf16_fused_supported(int T, int d, int E) { return gate_bf16_supported(d, E) && T >= 2048; }
 
-int launch_gate_bf16_fused(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E, int k,
-                           int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws, int32_t* scratch,
-                           int* tokens_per_hist, const int32_t** hist_out, const int32_t** coarse_out, hipStream_t s) {
-    if (!gate_bf16_fused_supported(T, d, E) || !frag_ws || !scratch || k < 1 || k > 2) return MOE_ERR_INVALID_ARG;
+int launch_gate_bf16_fused(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T,
+                           int d, int E, int k, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws,
+                           int32_t* scratch, int* tokens_per_hist, const int32_t** hist_out, hipStream_t s) {
+    if (!gate_bf16_fused_supported(T, d, E) || (!frag_ws && !Wg_packed) || !scratch || k < 1 || k > 2)
+        return MOE_ERR_INVALID_ARG;
     const int KB = d / kKB, ET = padded_expert_tiles(E);
-    uint16_t* frags = static_cast<uint16_t*>(frag_ws);
+    const uint16_t* frags = static_cast<const uint16_t*>(Wg_packed);
     // 64-token tiles once they give every CU a work-group, else 32-token ones
     const int MA = (T + 63) / 64 >= 256 ? 4 : 2;
     const int TM = 16 * MA;
-    const int nfine = (T + TM - 1) / TM, ncoarse = (T + kRouteTokens - 1) / kRouteTokens;
-    int32_t* hist = scratch;
-    int32_t* coarse = scratch + (size_t)nfine * k * E;            // within route_scratch_ints(T, E, k)
-    int rc = launch_prepare(Wg, frags, d, E, KB, ET, coarse, ncoarse * k * E, s);
-    if (rc != MOE_OK) return rc;
+    int32_t* hist = scratch;                                      // one histogram per tile: route_scratch_ints(T, E, k)
+    int rc = MOE_OK;
+    if (!frags) {
+        rc = launch_prepare(Wg, static_cast<uint16_t*>(frag_ws), d, E, KB, ET, s);
+        if (rc != MOE_OK) return rc;
+        frags = static_cast<const uint16_t*>(frag_ws);
+    }
     const uint16_t* xb = static_cast<const uint16_t*>(x);
     rc = MOE_ERR_INVALID_ARG;
 #define MOE_GATE_CASE(ma, ne, kk) \
     if (MA == ma && ET == ne && k == kk) \
-    rc = launch_cfg<ma, ne, kk>(xb, frags, bg, logits, T, d, E, ET, expert_idx, slot_idx, gate_w, hist, coarse, s)
+    rc = launch_cfg<ma, ne, kk>(xb, frags, bg, logits, T, d, E, ET, expert_idx, slot_idx, gate_w, hist, s)
     MOE_GATE_CASE(4, 8, 1); MOE_GATE_CASE(4, 4, 1); MOE_GATE_CASE(4, 2, 1); MOE_GATE_CASE(4, 1, 1);
     MOE_GATE_CASE(2, 8, 1); MOE_GATE_CASE(2, 4, 1); MOE_GATE_CASE(2, 2, 1); MOE_GATE_CASE(2, 1, 1);
     MOE_GATE_CASE(4, 8, 2); MOE_GATE_CASE(4, 4, 2); MOE_GATE_CASE(4, 2, 2); MOE_GATE_CASE(4, 1, 2);
@@ -392,7 +397,6 @@ int launch_gate_bf16_fused(const void* x, const float* Wg, const float* bg, floa
 #undef MOE_GATE_CASE
     *tokens_per_hist = TM;
     *hist_out = hist;
-    *coarse_out = coarse;
     return rc;
 }
 

@@ -67,16 +67,18 @@ int launch_gate_logits(const void* x, int dtype, const float* Wg, const float* b
 // frag_ws: gate_bf16_ws_bytes(d, E) bytes of scratch for the split weights, rewritten by every call
 bool gate_bf16_supported(int d, int E);
 size_t gate_bf16_ws_bytes(int d, int E);
-int launch_gate_logits_bf16(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E,
-                            void* frag_ws, hipStream_t s);
+int launch_gate_logits_bf16(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T,
+                            int d, int E, void* frag_ws, hipStream_t s);
+// the split weights written once into a caller-owned buffer of gate_bf16_ws_bytes(d, E) bytes (Wg_packed above)
+int launch_pack_gate(const float* Wg, void* packed, int d, int E, hipStream_t s);
 
-// logits, top-k, gate weights, tile-local ranks (parked in slot_idx) and histograms for bf16 tokens in two
-// launches; launch_route_finalize(..., *tokens_per_hist, ..., *hist_out, *coarse_out) completes the routing.
+// logits, top-k, gate weights, tile-local ranks (parked in slot_idx) and per-tile histograms for bf16 tokens;
+// launch_route_finalize(..., *tokens_per_hist, ..., *hist_out) completes the routing.
 // scratch as for launch_route; logits is always written
 bool gate_bf16_fused_supported(int T, int d, int E);
-int launch_gate_bf16_fused(const void* x, const float* Wg, const float* bg, float* logits, int T, int d, int E, int k,
-                           int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws, int32_t* scratch,
-                           int* tokens_per_hist, const int32_t** hist_out, const int32_t** coarse_out, hipStream_t s);
+int launch_gate_bf16_fused(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T,
+                           int d, int E, int k, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws,
+                           int32_t* scratch, int* tokens_per_hist, const int32_t** hist_out, hipStream_t s);
 
 // number of int32 the routing kernels need as scratch
 size_t route_scratch_ints(int T, int E, int k);
@@ -88,10 +90,10 @@ int launch_route(const float* logits, int T, int E, int k, int C,
                  int32_t* scratch, hipStream_t s);
 
 // second routing kernel alone: hist = one histogram [k][E] per block of TB tokens (TB divides 256) with the
-// block-local ranks parked in slot_idx, coarse = one per 256 tokens (sums of the fine ones; == hist for TB 256)
+// block-local ranks parked in slot_idx
 int launch_route_finalize(int T, int E, int k, int C, int TB, const int32_t* expert_idx, int32_t* slot_idx,
                           int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order, const int32_t* hist,
-                          const int32_t* coarse, hipStream_t s);
+                          hipStream_t s);
 
 // order[rank] = expert, ranked by min(expert_rows, C) descending (ties by index)
 int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s);

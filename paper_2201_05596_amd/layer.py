@@ -22,8 +22,12 @@ class MoELayer:
             W1, W2 = B.moe_pack_weights(W1), B.moe_pack_weights(W2)
             if residual:
                 Wd1, Wd2 = B.moe_pack_weights(Wd1), B.moe_pack_weights(Wd2)
-        self.shape = B.make_shape(T, d_model, d_ffn, E, top_k, capacity, dtype, residual,
-                                  B.MOE_FLAG_PACKED_WEIGHTS if pack_weights else 0)
+        flags = B.MOE_FLAG_PACKED_WEIGHTS if pack_weights else 0
+        if pack_weights:
+            packed_gate = B.moe_pack_gate(Wg)           # None: shape outside the bf16 gate kernel, Wg stays plain
+            if packed_gate is not None:
+                Wg, flags = packed_gate, flags | B.MOE_FLAG_PACKED_GATE
+        self.shape = B.make_shape(T, d_model, d_ffn, E, top_k, capacity, dtype, residual, flags)
         self.weights = (Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2)
         dev = W1.device
         el = torch.float32 if self.shape.dtype == B.MOE_F32 else torch.bfloat16

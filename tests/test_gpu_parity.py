@@ -114,6 +114,17 @@ def test_gate_from_tokens(dtype, T, d, E, k, C, bias, dup):
     if dup:                         # the tie is exact on the GPU too, and the lower index wins
         assert np.array_equal(lg[:, E - 1], lg[:, 1]) and np.array_equal(lg[:, E // 2], lg[:, 0])
     U.assert_routing_equal(r, orc.gate(lg, k, C))     # routing bit-exact on the GPU's own fp32 logits
+    packed = m.moe_pack_gate(Wg) if dtype == "bf16" else None
+    if packed is not None:          # the same call on gate weights split once beforehand: identical bits everywhere
+        pshape = m.make_shape(T, d, 8, E, k, C, dtype, flags=m.MOE_FLAG_PACKED_GATE)
+        logits2 = torch.full((T, E), 7.0, dtype=torch.float32, device=DEV)
+        r2 = {n: torch.full_like(v, -7) for n, v in r.items()}
+        m.moe_gate(pshape, x, packed, bg, logits2, r2["expert_idx"], r2["slot_idx"], r2["gate_w"], r2["expert_rows"],
+                   r2["slot_token"], ws)
+        torch.cuda.synchronize()
+        assert torch.equal(logits2, logits)
+        for n in r:
+            assert torch.equal(r2[n], r[n]), n
 
 
 # ------------------------------------------------------------------ dispatch / ffn / combine

@@ -47,7 +47,7 @@ def test_workspace_bytes():
 
 BAD_SHAPES = [
     (dict(T=0), -1), (dict(E=0), -1), (dict(capacity=0), -1), (dict(top_k=0), -1), (dict(top_k=200), -1),
-    (dict(dtype=5), -1), (dict(residual=2), -1), (dict(flags=2), -1), (dict(flags=1, dtype=0), -2),
+    (dict(dtype=5), -1), (dict(residual=2), -1), (dict(flags=4), -1), (dict(flags=1, dtype=0), -2), (dict(flags=2, dtype=0), -2), (dict(flags=2, E=200), -2),
     (dict(top_k=3), -2), (dict(E=2048), -2), (dict(d_model=1028), -2), (dict(d_ffn=4100), -2),
 ]
 
