@@ -143,6 +143,7 @@ def time_config(cfg, steps, warmup, pack):
         "weights": f"packed once by moe_pack_weights, outside the timed region (layer set-up {setup_ms:.1f} ms)" if pack
                    else "plain [E,d,f] / [E,f,d]",
         "kept_rows": alg["kept_rows"], "touched_experts": alg["touched_experts"],
+        "expert_rows": [int(r) for r in rows],
         "roofline": roofline,
         "layer_roofline": {"hbm_GBps": layer_gbs, "hbm_frac": layer_gbs / HBM_PEAK_GBS, "mfma_TFLOPs": layer_tflops,
                            "mfma_frac": layer_tflops / MFMA_BF16_PEAK_TFLOPS, "binding_frac":
@@ -307,8 +308,8 @@ def main() -> int:
         "config": {"workload": head["workload"], "weights": head["weights"], "kept_rows": head["kept_rows"], "touched_experts": head["touched_experts"]},
         "roofline": head["roofline"],
         "layer_roofline": head["layer_roofline"],
-        "stage_ms": head["stage_ms"],
-        "configs": {n: configs[n] for n in ALL_CONFIGS if n in configs} if not args.only else {},
+        "stage_ms": head["stage_ms"], "expert_rows": head["expert_rows"],
+        "configs": {n: configs[n] for n in ALL_CONFIGS if n in configs},
         "extras": extras,
     }
     if not args.no_cpu_baseline:
