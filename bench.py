@@ -49,7 +49,12 @@ ALL_CONFIGS = ("c2", "c3a", "c3b", "c4", "c5")
 # HBM traffic per launch (bytes) of a workload's longest kernel: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
 # each scaled by what the same counter reads for a plain copy of known size.  Measured in separate runs
 # (profiles/*.md name the commands), not in this process.
-PROFILED_TRAFFIC = {
+PROFILED_TRAFFIC = {          # profiles/hbm_traffic_all_configs.md
+    ("c2", "expert_gemm1"): 1161700000, ("c2", "expert_gemm2"): 1162500000,
+    ("c3a", "expert_gemm2"): 348900000, ("c3a", "expert_gemm1"): 283900000,
+    ("c3b", "expert_gemm1"): 617200000, ("c3b", "expert_gemm2"): 617200000,
+    ("c4", "expert_gemm1"): 1628100000, ("c4", "expert_gemm2"): 1613400000,
+    ("c5", "expert_gemm1"): 9231000000, ("c5", "expert_gemm2"): 10946900000,
 }
 
 
@@ -132,7 +137,8 @@ def time_config(cfg, steps, warmup, pack):
         achieved = work / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     traffic = PROFILED_TRAFFIC.get((cfg.name, dom))
     roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                "traffic": traffic, "traffic_source": "rocprofv3 --pmc, separate run (profiles/)" if traffic else None,
+                "traffic": traffic, "traffic_source": "rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, separate runs on packed weights "
+                                  "(profiles/hbm_traffic_all_configs.md); not measured in this process" if traffic else None,
                 "algorithmic_work_per_launch": work, "avg_ms": dom_ms, "timed_launches": ncalls,
                 "t_floor_hbm_us": t_hbm * 1e6, "t_floor_mfma_us": t_mfma * 1e6}
     layer_gbs = alg["layer_bytes"] / (ms_per_step * 1e-3) / 1e9
