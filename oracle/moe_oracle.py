@@ -21,8 +21,8 @@ logits; everything else is fp64.  bf16 inputs arrive already widened (exactly)
 to float32/float64 arrays; no intermediate bf16 rounding is emulated.
 
 Readings where the paper is silent (each also listed in the design notes):
-  * gate = softmax over all E logits, no noise (Sec. 5.4 speaks of gating
-    logits "in the probability domain").
+  * gate = softmax over all E logits, no noise (Sec. 5.4: the gate's logits
+    are turned into probabilities before they scale the expert output).
   * top-k by logit value, lowest expert index wins ties.
   * top-1 weight = softmax probability of the chosen expert; top-2 weights =
     the two chosen probabilities renormalised to sum to one, before any drop.
