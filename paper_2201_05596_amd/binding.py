@@ -133,16 +133,45 @@ def make_shape(T: int, d_model: int, d_ffn: int, E: int, top_k: int, capacity: i
     return MoeShape(T, d_model, d_ffn, E, top_k, capacity, int(dtype), int(bool(residual)), int(flags))
 
 
-def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> Optional[int]:
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None, numel: Optional[int] = None,
+         name: str = "tensor") -> Optional[int]:
+    """Device address of a tensor argument after checking what the C ABI cannot: device, contiguity, dtype and, when
+    `numel` is given, the element count (a buffer sized for another shape would be indexed out of bounds on the GPU)."""
     if t is None:
         return None
     if not t.is_cuda:
-        raise ValueError("device tensor required")
+        raise ValueError(f"{name}: device tensor required")
     if not t.is_contiguous():
-        raise ValueError("contiguous tensor required")
+        raise ValueError(f"{name}: contiguous tensor required")
     if dtype is not None and t.dtype != dtype:
-        raise ValueError(f"expected {dtype}, got {t.dtype}")
+        raise ValueError(f"{name}: expected {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name}: expected {numel} elements for this shape, got {t.numel()}")
     return t.data_ptr()
+
+
+def _ws(shape, ws, need: Optional[int] = None):
+    """(address, bytes) of a workspace tensor; `need`: the byte count the call requires (checked here as well)."""
+    if ws is None:
+        return None, 0
+    nbytes = ws.numel() * ws.element_size()
+    if need is not None and nbytes < need:
+        raise ValueError(f"workspace: {nbytes} bytes, this shape needs {need}")
+    return _ptr(ws, name="ws"), nbytes
+
+
+def _w(shape, G: int, K: int, N: int) -> int:
+    """Elements of an FFN weight array [G,K,N]: plain, or as moe_pack_weights lays it out."""
+    if shape.flags & MOE_FLAG_PACKED_WEIGHTS:
+        return G * ((K + 31) // 32) * ((N + 127) // 128) * 4096
+    return G * K * N
+
+
+def _wg(shape) -> int:
+    """float32 elements of the gate weights: plain [d,E], or the buffer moe_pack_gate returns."""
+    if shape.flags & MOE_FLAG_PACKED_GATE:
+        return (moe_packed_gate_bytes(shape.d_model, shape.E) + 3) // 4
+    return shape.d_model * shape.E
 
 
 def _stream() -> int:
@@ -205,21 +234,26 @@ def moe_pack_gate(Wg: torch.Tensor) -> Optional[torch.Tensor]:
     return packed
 
 
-def moe_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws) -> None:
+def _gate_args(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token):
     i32, f32 = torch.int32, torch.float32
-    rc = load_library().moe_gate(
-        ctypes.byref(shape), _ptr(x, _elem(shape) if x is not None else None), _ptr(Wg, f32), _ptr(bg, f32),
-        _ptr(logits, f32), _ptr(expert_idx, i32), _ptr(slot_idx, i32), _ptr(gate_w, f32), _ptr(expert_rows, i32),
-        _ptr(slot_token, i32), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    T, d, E, k, C = shape.T, shape.d_model, shape.E, shape.top_k, shape.capacity
+    return (_ptr(x, _elem(shape) if x is not None else None, T * d, "x"),
+            _ptr(Wg, f32, _wg(shape) if x is not None else None, "Wg"), _ptr(bg, f32, E, "bg"),
+            _ptr(logits, f32, T * E, "logits"), _ptr(expert_idx, i32, T * k, "expert_idx"),
+            _ptr(slot_idx, i32, T * k, "slot_idx"), _ptr(gate_w, f32, T * k, "gate_w"),
+            _ptr(expert_rows, i32, E, "expert_rows"), _ptr(slot_token, i32, E * C, "slot_token"))
+
+
+def moe_gate(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token, ws) -> None:
+    wsp, wsn = _ws(shape, ws, moe_workspace_bytes(shape))
+    rc = load_library().moe_gate(ctypes.byref(shape), *_gate_args(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w,
+                                                                 expert_rows, slot_token), wsp, wsn, _stream())
     _check("moe_gate", rc)
 
 
 def moe_gate_noalloc(shape, x, Wg, bg, logits, expert_idx, slot_idx, gate_w, expert_rows, slot_token) -> None:
-    i32, f32 = torch.int32, torch.float32
-    rc = load_library().moe_gate_noalloc(
-        ctypes.byref(shape), _ptr(x, _elem(shape) if x is not None else None), _ptr(Wg, f32), _ptr(bg, f32),
-        _ptr(logits, f32), _ptr(expert_idx, i32), _ptr(slot_idx, i32), _ptr(gate_w, f32), _ptr(expert_rows, i32),
-        _ptr(slot_token, i32), _stream())
+    rc = load_library().moe_gate_noalloc(ctypes.byref(shape), *_gate_args(shape, x, Wg, bg, logits, expert_idx, slot_idx,
+                                                                         gate_w, expert_rows, slot_token), _stream())
     _check("moe_gate_noalloc", rc)
 
 
@@ -233,52 +267,74 @@ def moe_gate_noalloc_max_bytes() -> int:
 
 def moe_dispatch(shape, x, slot_token, expert_rows, xe) -> None:
     el = _elem(shape)
-    rc = load_library().moe_dispatch(ctypes.byref(shape), _ptr(x, el), _ptr(slot_token, torch.int32),
-                                     _ptr(expert_rows, torch.int32), _ptr(xe, el), _stream())
+    T, d, E, C = shape.T, shape.d_model, shape.E, shape.capacity
+    rc = load_library().moe_dispatch(ctypes.byref(shape), _ptr(x, el, T * d, "x"),
+                                     _ptr(slot_token, torch.int32, E * C, "slot_token"),
+                                     _ptr(expert_rows, torch.int32, E, "expert_rows"), _ptr(xe, el, E * C * d, "xe"), _stream())
     _check("moe_dispatch", rc)
 
 
 def moe_expert_ffn(shape, xe, expert_rows, W1, b1, W2, b2, ye, ws) -> None:
     el = _elem(shape)
+    d, f, E, C = shape.d_model, shape.d_ffn, shape.E, shape.capacity
+    wsp, wsn = _ws(shape, ws, moe_workspace_bytes(shape))
     rc = load_library().moe_expert_ffn(
-        ctypes.byref(shape), _ptr(xe, el), _ptr(expert_rows, torch.int32), _ptr(W1, el), _ptr(b1, el), _ptr(W2, el),
-        _ptr(b2, el), _ptr(ye, el), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+        ctypes.byref(shape), _ptr(xe, el, E * C * d, "xe"), _ptr(expert_rows, torch.int32, E, "expert_rows"),
+        _ptr(W1, el, _w(shape, E, d, f), "W1"), _ptr(b1, el, E * f, "b1"), _ptr(W2, el, _w(shape, E, f, d), "W2"),
+        _ptr(b2, el, E * d, "b2"), _ptr(ye, el, E * C * d, "ye"), wsp, wsn, _stream())
     _check("moe_expert_ffn", rc)
 
 
 def moe_expert_ffn_slice(shape, xe, expert_rows, W1s, b1s, W2s, ye_partial, ws) -> None:
     el = _elem(shape)
+    d, f, E, C = shape.d_model, shape.d_ffn, shape.E, shape.capacity
+    wsp, wsn = _ws(shape, ws, moe_workspace_bytes(shape))
     rc = load_library().moe_expert_ffn_slice(
-        ctypes.byref(shape), _ptr(xe, el), _ptr(expert_rows, torch.int32), _ptr(W1s, el), _ptr(b1s, el), _ptr(W2s, el),
-        _ptr(ye_partial, torch.float32), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+        ctypes.byref(shape), _ptr(xe, el, E * C * d, "xe"), _ptr(expert_rows, torch.int32, E, "expert_rows"),
+        _ptr(W1s, el, _w(shape, E, d, f), "W1s"), _ptr(b1s, el, E * f, "b1s"), _ptr(W2s, el, _w(shape, E, f, d), "W2s"),
+        _ptr(ye_partial, torch.float32, E * C * d, "ye_partial"), wsp, wsn, _stream())
     _check("moe_expert_ffn_slice", rc)
 
 
 def moe_expert_ffn_slice_reduce(shape, n_slices, ye_partials, expert_rows, b2, ye) -> None:
     el = _elem(shape)
+    d, E, C = shape.d_model, shape.E, shape.capacity
     rc = load_library().moe_expert_ffn_slice_reduce(
-        ctypes.byref(shape), int(n_slices), _ptr(ye_partials, torch.float32), _ptr(expert_rows, torch.int32), _ptr(b2, el),
-        _ptr(ye, el), _stream())
+        ctypes.byref(shape), int(n_slices), _ptr(ye_partials, torch.float32, int(n_slices) * E * C * d, "ye_partials"),
+        _ptr(expert_rows, torch.int32, E, "expert_rows"), _ptr(b2, el, E * d, "b2"), _ptr(ye, el, E * C * d, "ye"), _stream())
     _check("moe_expert_ffn_slice_reduce", rc)
 
 
 def moe_combine(shape, ye, expert_idx, slot_idx, gate_w, addend, out) -> None:
     el = _elem(shape)
-    rc = load_library().moe_combine(ctypes.byref(shape), _ptr(ye, el), _ptr(expert_idx, torch.int32),
-                                    _ptr(slot_idx, torch.int32), _ptr(gate_w, torch.float32), _ptr(addend, el),
-                                    _ptr(out, el), _stream())
+    T, d, E, k, C = shape.T, shape.d_model, shape.E, shape.top_k, shape.capacity
+    rc = load_library().moe_combine(ctypes.byref(shape), _ptr(ye, el, E * C * d, "ye"),
+                                    _ptr(expert_idx, torch.int32, T * k, "expert_idx"),
+                                    _ptr(slot_idx, torch.int32, T * k, "slot_idx"), _ptr(gate_w, torch.float32, T * k, "gate_w"),
+                                    _ptr(addend, el, T * d, "addend"), _ptr(out, el, T * d, "out"), _stream())
     _check("moe_combine", rc)
+
+
+def _ffn_weight_args(shape, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2):
+    el = _elem(shape)
+    d, f, E = shape.d_model, shape.d_ffn, shape.E
+    return (_ptr(W1, el, _w(shape, E, d, f), "W1"), _ptr(b1, el, E * f, "b1"), _ptr(W2, el, _w(shape, E, f, d), "W2"),
+            _ptr(b2, el, E * d, "b2"), _ptr(Wd1, el, _w(shape, 1, d, f), "Wd1"), _ptr(bd1, el, f, "bd1"),
+            _ptr(Wd2, el, _w(shape, 1, f, d), "Wd2"), _ptr(bd2, el, d, "bd2"))
 
 
 def moe_layer_forward(shape, x, Wg, bg, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2, out,
                       logits_out, expert_idx_out, slot_idx_out, gate_w_out, expert_rows_out, slot_token_out, ws) -> None:
     el, i32, f32 = _elem(shape), torch.int32, torch.float32
+    T, d, E, k, C = shape.T, shape.d_model, shape.E, shape.top_k, shape.capacity
+    wsp, wsn = _ws(shape, ws, moe_workspace_bytes(shape))
     rc = load_library().moe_layer_forward(
-        ctypes.byref(shape), _ptr(x, el), _ptr(Wg, f32), _ptr(bg, f32), _ptr(W1, el), _ptr(b1, el), _ptr(W2, el),
-        _ptr(b2, el), _ptr(Wd1, el), _ptr(bd1, el), _ptr(Wd2, el), _ptr(bd2, el), _ptr(out, el),
-        _ptr(logits_out, f32), _ptr(expert_idx_out, i32), _ptr(slot_idx_out, i32), _ptr(gate_w_out, f32),
-        _ptr(expert_rows_out, i32), _ptr(slot_token_out, i32),
-        _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+        ctypes.byref(shape), _ptr(x, el, T * d, "x"), _ptr(Wg, f32, _wg(shape), "Wg"), _ptr(bg, f32, E, "bg"),
+        *_ffn_weight_args(shape, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2), _ptr(out, el, T * d, "out"),
+        _ptr(logits_out, f32, T * E, "logits_out"), _ptr(expert_idx_out, i32, T * k, "expert_idx_out"),
+        _ptr(slot_idx_out, i32, T * k, "slot_idx_out"), _ptr(gate_w_out, f32, T * k, "gate_w_out"),
+        _ptr(expert_rows_out, i32, E, "expert_rows_out"), _ptr(slot_token_out, i32, E * C, "slot_token_out"),
+        wsp, wsn, _stream())
     _check("moe_layer_forward", rc)
 
 
@@ -290,12 +346,20 @@ def moe_decode_block_forward(shape, block, weights: dict, x, k_cache, v_cache, p
                              ws) -> None:
     """`weights`: name -> tensor (or None) for the fields of moe_block_weights_t."""
     el, f32 = _elem(shape), torch.float32
-    kinds = {"ln1_gamma": f32, "ln1_beta": f32, "ln2_gamma": f32, "ln2_beta": f32, "Wg": f32, "bg": f32}
-    w = MoeBlockWeights(**{n: _ptr(weights.get(n), kinds.get(n, el)) for n in BLOCK_WEIGHT_FIELDS})
+    T, d, f, E = shape.T, shape.d_model, shape.d_ffn, shape.E
+    cache = T * d * block.max_len                      # [T, H, max_len, d/H]
+    sizes = {"ln1_gamma": (f32, d), "ln1_beta": (f32, d), "ln2_gamma": (f32, d), "ln2_beta": (f32, d),
+             "Wqkv": (el, 3 * d * d), "bqkv": (el, 3 * d), "Wo": (el, d * d), "bo": (el, d),
+             "Wg": (f32, _wg(shape)), "bg": (f32, E), "W1": (el, _w(shape, E, d, f)), "b1": (el, E * f),
+             "W2": (el, _w(shape, E, f, d)), "b2": (el, E * d), "Wd1": (el, _w(shape, 1, d, f)), "bd1": (el, f),
+             "Wd2": (el, _w(shape, 1, f, d)), "bd2": (el, d)}
+    w = MoeBlockWeights(**{n: _ptr(weights.get(n), sizes[n][0], sizes[n][1], n) for n in BLOCK_WEIGHT_FIELDS})
+    wsp, wsn = _ws(shape, ws, moe_decode_block_workspace_bytes(shape, block))
     rc = load_library().moe_decode_block_forward(
-        ctypes.byref(shape), ctypes.byref(block), ctypes.byref(w), _ptr(x, el), _ptr(k_cache, el), _ptr(v_cache, el),
-        _ptr(pos, torch.int32), _ptr(out, el), _ptr(x1_out, el), _ptr(moe_in_out, el), _ptr(logits_out, f32),
-        _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+        ctypes.byref(shape), ctypes.byref(block), ctypes.byref(w), _ptr(x, el, T * d, "x"),
+        _ptr(k_cache, el, cache, "k_cache"), _ptr(v_cache, el, cache, "v_cache"), _ptr(pos, torch.int32, T, "pos"),
+        _ptr(out, el, T * d, "out"), _ptr(x1_out, el, T * d, "x1_out"), _ptr(moe_in_out, el, T * d, "moe_in_out"),
+        _ptr(logits_out, f32, T * E, "logits_out"), wsp, wsn, _stream())
     _check("moe_decode_block_forward", rc)
 
 

@@ -92,3 +92,50 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros((4, 8))
     with pytest.raises(ValueError):
         B.moe_dispatch(s, x, x, x, x)
+
+
+class _FakeDeviceTensor:
+    """Stands in for a CUDA tensor so that the binding's argument checks can run without a GPU."""
+
+    def __init__(self, numel, dtype, contiguous=True):
+        import torch
+        self._n, self.dtype, self._c, self.is_cuda = numel, dtype, contiguous, True
+        self._torch = torch
+
+    def is_contiguous(self):
+        return self._c
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return {self._torch.float32: 4, self._torch.int32: 4, self._torch.bfloat16: 2, self._torch.uint8: 1}[self.dtype]
+
+    def data_ptr(self):
+        return 0x1000
+
+
+def test_binding_checks_element_counts_before_calling_the_library():
+    """A buffer sized for another shape must be refused on the host: the kernels index by T/E/C/d/f."""
+    import torch
+    s = B.make_shape(64, 256, 512, 8, 1, 16, "bf16")
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    ok = dict(x=_FakeDeviceTensor(64 * 256, bf), slot_token=_FakeDeviceTensor(8 * 16, i32),
+              expert_rows=_FakeDeviceTensor(8, i32), xe=_FakeDeviceTensor(8 * 16 * 256, bf))
+    for bad_name, bad in (("slot_token", _FakeDeviceTensor(8 * 32, i32)),       # a table built for another capacity
+                          ("xe", _FakeDeviceTensor(8 * 16 * 128, bf)), ("x", _FakeDeviceTensor(64 * 256, f32)),
+                          ("expert_rows", _FakeDeviceTensor(8, i32, contiguous=False))):
+        args = dict(ok)
+        args[bad_name] = bad
+        with pytest.raises(ValueError, match=bad_name):
+            B.moe_dispatch(s, args["x"], args["slot_token"], args["expert_rows"], args["xe"])
+    # a workspace allocated for a smaller shape
+    small = B.moe_workspace_bytes(B.make_shape(8, 256, 512, 8, 1, 2, "bf16"))
+    assert small < B.moe_workspace_bytes(s)
+    with pytest.raises(ValueError, match="workspace"):
+        B.moe_expert_ffn(s, _FakeDeviceTensor(8 * 16 * 256, bf), ok["expert_rows"], _FakeDeviceTensor(8 * 256 * 512, bf), None,
+                         _FakeDeviceTensor(8 * 512 * 256, bf), None, _FakeDeviceTensor(8 * 16 * 256, bf),
+                         _FakeDeviceTensor(small, torch.uint8))
+    # packed weights have their own element count
+    sp = B.make_shape(64, 256, 520, 8, 1, 16, "bf16", flags=B.MOE_FLAG_PACKED_WEIGHTS)
+    assert B._w(sp, 8, 256, 520) == 8 * 8 * 5 * 4096 and B._w(s, 8, 256, 512) == 8 * 256 * 512
