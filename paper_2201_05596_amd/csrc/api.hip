@@ -111,7 +111,7 @@ FfnPlan plan_ffn(const moe_shape_t* s) {
 
 // Carving of the caller's workspace.  Offsets in bytes; every region 256-byte aligned.
 struct WsLayout {
-    size_t logits, wg_frags, hist, expert_idx, slot_idx, gate_w, rows, order, slot_token, xe, h, ye, hd, dense, partial, total;
+    size_t logits, wg_frags, hist, flags, expert_idx, slot_idx, gate_w, rows, order, slot_token, xe, h, ye, hd, dense, partial, total;
 };
 
 WsLayout ws_layout(const moe_shape_t* s) {
@@ -124,6 +124,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.logits = take(T * E * 4);
     L.wg_frags = take(s->dtype == MOE_BF16 ? gate_bf16_ws_bytes(s->d_model, s->E) : 0);
     L.hist = take(route_scratch_ints(s->T, s->E, s->top_k) * 4);
+    L.flags = take(kGateFlagInts * 4);                 // hand-over flags of the one-launch decode gate
     L.expert_idx = take(T * k * 4);
     L.slot_idx = take(T * k * 4);
     L.gate_w = take(T * k * 4);
@@ -201,6 +202,18 @@ int run_gate(const moe_shape_t* s, const void* x, const float* Wg, const float* 
         rc = launch_route_finalize(s->T, s->E, s->top_k, s->capacity, tb, expert_idx, slot_idx, rows, slot_token, order,
                                    hist, st);
         if (profile) prof_mark(ST_ROUTE, st);
+        return rc;
+    }
+    if (s->dtype == MOE_BF16 && gate_decode_supported(s->T, s->d_model, s->E)) {
+        // decode: logits and the whole routing in one launch (counted under ST_LOGITS)
+        static uint32_t epoch = 0;                     // never repeats: a flag left by an earlier call is never "done"
+        epoch = epoch + 1 == 0 ? 1 : epoch + 1;
+        const bool packed = s->flags & MOE_FLAG_PACKED_GATE;
+        if (profile) prof_pre(ST_LOGITS, st);
+        rc = launch_gate_decode(x, packed ? nullptr : Wg, packed ? Wg : nullptr, bg, logits, s->T, s->d_model, s->E,
+                                s->top_k, s->capacity, expert_idx, slot_idx, gate_w, rows, slot_token, order,
+                                at<void>(ws, L.wg_frags), at<uint32_t>(ws, L.flags), epoch, st);
+        if (profile) prof_mark(ST_LOGITS, st);
         return rc;
     }
     if (profile) prof_pre(ST_LOGITS, st);

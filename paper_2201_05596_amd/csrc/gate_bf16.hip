@@ -27,7 +27,7 @@
 //     With few tokens the experts are split over work-groups instead (K = 0: logits only) so that
 //     more CUs take part, and the routing runs as a kernel of its own.
 // Requires d_model to be a multiple of 32 and at most 128 experts; other shapes use the fp32 kernel.
-#include "gate_common.h"
+#include "route_device.h"
 
 namespace moe {
 
@@ -90,14 +90,13 @@ template <int MA, int NE, int K> struct GateLds {
 };
 
 template <int MA, int NE, int K>
-__global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ frags,
-                                                        const float* __restrict__ bg, float* __restrict__ logits, int T, int d,
-                                                        int E, int ET, int32_t* __restrict__ expert_idx,
-                                                        int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
-                                                        int32_t* __restrict__ hist) {
+__device__ __forceinline__ void gate_bf16_body(char* lds, const uint16_t* __restrict__ x, const uint16_t* __restrict__ frags,
+                                               const float* __restrict__ bg, float* __restrict__ logits, int T, int d,
+                                               int E, int ET, int32_t* __restrict__ expert_idx,
+                                               int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
+                                               int32_t* __restrict__ hist) {
     typedef GateLds<MA, NE, K> L;
     constexpr int D = GateCfg<MA, NE>::D, PER = GateCfg<MA, NE>::PER, WK = 4, TM = L::TM, TN = L::TN, STRIDE = L::STRIDE;
-    extern __shared__ __attribute__((aligned(16))) char lds[];
     f32x4_t* red = reinterpret_cast<f32x4_t*>(lds);               // [2][MA][NE][64]
     float* tile = reinterpret_cast<float*>(lds);                  // [TM][STRIDE], after the reduction
 
@@ -294,6 +293,55 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
 }
 
 template <int MA, int NE, int K>
+__global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ frags,
+                                                        const float* __restrict__ bg, float* __restrict__ logits, int T, int d,
+                                                        int E, int ET, int32_t* __restrict__ expert_idx,
+                                                        int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
+                                                        int32_t* __restrict__ hist) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    gate_bf16_body<MA, NE, K>(lds, x, frags, bg, logits, T, d, E, ET, expert_idx, slot_idx, gate_w, hist);
+}
+
+// The whole gate of a decode step (at most 256 tokens) in ONE launch: the work-groups compute the logits tile by tile
+// (experts split over work-groups, so that many CUs share the read of the gate weights); every work-group then
+// publishes a flag, and the one with the highest index waits for all flags and runs the whole routing on the finished
+// logits.  The flags hold the call's epoch (a number the host never repeats for a workspace), so they need no
+// clearing: whatever an earlier call or nobody left there is not this call's epoch.  Hand-over across the XCDs'
+// separate L2s: the writers release at device scope after their stores (write-back of the L2), the reader acquires at
+// device scope before its loads (invalidate).  The wait cannot hang: work-groups are started in index order, so all
+// others are running or done when the last one starts (and the whole grid, at most 64 work-groups, fits on the chip
+// at once); it is bounded all the same, and gives up (leaving wrong tables, never a hung GPU) after about 10^6 polls.
+template <int MA, int NE, int RK, int NV>
+__global__ __launch_bounds__(256) void gate_decode_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ frags,
+                                                          const float* __restrict__ bg, float* __restrict__ logits, int T,
+                                                          int d, int E, int ET, int C, int32_t* __restrict__ expert_idx,
+                                                          int32_t* __restrict__ slot_idx, float* __restrict__ gate_w,
+                                                          int32_t* __restrict__ expert_rows, int32_t* __restrict__ slot_token,
+                                                          int32_t* __restrict__ expert_order, uint32_t* __restrict__ flags,
+                                                          uint32_t epoch) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    gate_bf16_body<MA, NE, 0>(lds, x, frags, bg, logits, T, d, E, ET, nullptr, nullptr, nullptr, nullptr);
+    const int nblocks = gridDim.x * gridDim.y, bid = blockIdx.y * gridDim.x + blockIdx.x;
+    __syncthreads();                                   // every thread's logits stores are issued
+    if (threadIdx.x == 0) {
+        __atomic_thread_fence(__ATOMIC_RELEASE);       // device scope: this work-group's stores become visible ...
+        __hip_atomic_store(flags + bid, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ... before its flag
+    }
+    if (bid != nblocks - 1) return;
+    if ((int)threadIdx.x < nblocks) {
+        int polls = 0;
+        while (__hip_atomic_load(flags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch && polls < (1 << 20)) {
+            __builtin_amdgcn_s_sleep(2);
+            ++polls;
+        }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);           // device scope: nothing read below comes from a stale cache line
+    __syncthreads();
+    route_single_body<RK, NV>(reinterpret_cast<int32_t*>(lds), logits, T, E, C, expert_idx, slot_idx, gate_w, expert_rows,
+                              slot_token, expert_order, nullptr);
+}
+
+template <int MA, int NE, int K>
 int launch_cfg(const uint16_t* x, const uint16_t* frags, const float* bg, float* logits, int T, int d, int E, int ET,
                int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* hist, hipStream_t s) {
     constexpr int smem = GateLds<MA, NE, K>::BYTES;
@@ -362,6 +410,60 @@ int launch_gate_logits_bf16(const void* x, const float* Wg, const void* Wg_packe
     MOE_GATE_CASE(2, 4); MOE_GATE_CASE(2, 2); MOE_GATE_CASE(2, 1);
 #undef MOE_GATE_CASE
     return MOE_ERR_INVALID_ARG;
+}
+
+// The decode gate in one launch: bf16 tokens, at most 256 of them.  flags: 64 uint32 of scratch; epoch: a value that
+// differs from what any earlier call left in `flags`.
+bool gate_decode_supported(int T, int d, int E) { return gate_bf16_supported(d, E) && T <= kRouteTokens; }
+
+template <int RK, int NV>
+static int launch_decode_cfg(const uint16_t* x, const uint16_t* frags, const float* bg, float* logits, int T, int d, int E,
+                             int ET, int C, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows,
+                             int32_t* slot_token, int32_t* expert_order, uint32_t* flags, uint32_t epoch, hipStream_t s) {
+    constexpr int MA = 2, NE = 1;                       // smallest tile: most work-groups (at most 8 x 8)
+    const size_t route = route_single_lds_ints(E, RK) * sizeof(int32_t);
+    const size_t smem = route > (size_t)GateLds<MA, NE, 0>::BYTES ? route : (size_t)GateLds<MA, NE, 0>::BYTES;
+    const dim3 grid((T + 16 * MA - 1) / (16 * MA), ET / NE);
+    if (grid.x * grid.y > 64) return MOE_ERR_INVALID_ARG;
+    static size_t attr_bytes = 0;                       // one per instantiation
+    if (smem > attr_bytes) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_decode_kernel<MA, NE, RK, NV>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_bytes = smem;
+    }
+    hipLaunchKernelGGL((gate_decode_kernel<MA, NE, RK, NV>), grid, dim3(256), smem, s, x, frags, bg, logits, T, d, E, ET, C,
+                       expert_idx, slot_idx, gate_w, expert_rows, slot_token, expert_order, flags, epoch);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int launch_gate_decode(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T, int d,
+                       int E, int k, int C, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows,
+                       int32_t* slot_token, int32_t* expert_order, void* frag_ws, uint32_t* flags, uint32_t epoch,
+                       hipStream_t s) {
+    if (!gate_decode_supported(T, d, E) || (!frag_ws && !Wg_packed) || !flags || k < 1 || k > 2) return MOE_ERR_INVALID_ARG;
+    const int KB = d / kKB, ET = padded_expert_tiles(E);
+    const uint16_t* frags = static_cast<const uint16_t*>(Wg_packed);
+    if (!frags) {
+        const int rc = launch_prepare(Wg, static_cast<uint16_t*>(frag_ws), d, E, KB, ET, s);
+        if (rc != MOE_OK) return rc;
+        frags = static_cast<const uint16_t*>(frag_ws);
+    }
+    const uint16_t* xb = static_cast<const uint16_t*>(x);
+#define MOE_DECODE_CASE(kk, nv) \
+    return launch_decode_cfg<kk, nv>(xb, frags, bg, logits, T, d, E, ET, C, expert_idx, slot_idx, gate_w, expert_rows, \
+                                     slot_token, expert_order, flags, epoch, s)
+    if (k == 1) {
+        if (E <= 16) MOE_DECODE_CASE(1, 1);
+        if (E <= 32) MOE_DECODE_CASE(1, 2);
+        if (E <= 64) MOE_DECODE_CASE(1, 4);
+        MOE_DECODE_CASE(1, 8);
+    }
+    if (E <= 16) MOE_DECODE_CASE(2, 1);
+    if (E <= 32) MOE_DECODE_CASE(2, 2);
+    if (E <= 64) MOE_DECODE_CASE(2, 4);
+    MOE_DECODE_CASE(2, 8);
+#undef MOE_DECODE_CASE
 }
 
 // With fewer tokens the fused kernel would leave most CUs idle; logits over expert groups plus a separate

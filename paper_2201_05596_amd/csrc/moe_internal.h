@@ -80,6 +80,15 @@ int launch_gate_bf16_fused(const void* x, const float* Wg, const void* Wg_packed
                            int d, int E, int k, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, void* frag_ws,
                            int32_t* scratch, int* tokens_per_hist, const int32_t** hist_out, hipStream_t s);
 
+// the whole gate of at most 256 bf16 tokens in one launch (logits by many work-groups, routing by the last one);
+// flags: kGateFlagInts uint32 of scratch, epoch: a value no earlier call left there
+constexpr int kGateFlagInts = 64;
+bool gate_decode_supported(int T, int d, int E);
+int launch_gate_decode(const void* x, const float* Wg, const void* Wg_packed, const float* bg, float* logits, int T, int d,
+                       int E, int k, int C, int32_t* expert_idx, int32_t* slot_idx, float* gate_w, int32_t* expert_rows,
+                       int32_t* slot_token, int32_t* expert_order, void* frag_ws, uint32_t* flags, uint32_t epoch,
+                       hipStream_t s);
+
 // number of int32 the routing kernels need as scratch
 size_t route_scratch_ints(int T, int E, int k);
 
