@@ -78,6 +78,10 @@ def test_gate_logits(dtype, T, d, E, bias):
     ("bf16", 16448, 64, 16, 1, 1100, False, False), ("bf16", 16500, 32, 100, 2, 250, True, True),
     ("bf16", 77, 2048, 128, 1, 1, True, False), ("bf16", 1000, 64, 30, 2, 50, True, True),
     ("bf16", 300, 520, 64, 1, 5, False, False), ("bf16", 500, 64, 200, 2, 4, False, True),
+    # at most 256 bf16 tokens, d % 32 == 0, E <= 128: the one-launch decode gate (1 to 64 work-groups)
+    ("bf16", 256, 64, 128, 2, 5, True, True), ("bf16", 33, 512, 16, 1, 9, False, False),
+    ("bf16", 255, 96, 17, 2, 40, True, True), ("bf16", 64, 2048, 128, 1, 1, False, "hot"), ("bf16", 2, 32, 3, 2, 1, True, False),
+    ("bf16", 31, 64, 100, 1, 2, True, True), ("bf16", 257, 64, 128, 1, 3, False, False),
     ("f32", 300, 100, 12, 2, 40, True, True)])
 def test_gate_from_tokens(dtype, T, d, E, k, C, bias, dup):
     m = U.amd()
