@@ -124,6 +124,12 @@ def time_config(cfg, steps, warmup, pack):
 
     rows = layer.routing["expert_rows"].cpu().numpy()
     alg = algorithmic_work(cfg, rows)
+    paired = []    # stages in which the dense branch's product ran inside the experts' launch: its work belongs there
+    for e, dn in (("expert_gemm1", "dense_gemm1"), ("expert_gemm2", "dense_gemm2")):
+        if cfg.residual and dn not in stage_ms and e in stage_ms:
+            alg["stage_flops"][e] += alg["stage_flops"][dn]
+            alg["stage_bytes"][e] += alg["stage_bytes"][dn]
+            paired.append(e)
     t_hbm = alg["layer_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = alg["layer_flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) if cfg.dtype == "bf16" else 0.0
     bound = "mfma" if t_mfma > t_hbm else "hbm"
@@ -136,7 +142,7 @@ def time_config(cfg, steps, warmup, pack):
         work, peak, unit = alg["stage_flops"].get(dom, 0), MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         achieved = work / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     traffic = PROFILED_TRAFFIC.get((cfg.name, dom))
-    roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+    roofline = {"bound": bound, "kernel": dom + (" (experts + dense branch in one launch)" if dom in paired else "") if dom else dom, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
                 "traffic": traffic, "traffic_source": "rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, separate runs on packed weights "
                                   "(profiles/hbm_traffic_all_configs.md); not measured in this process" if traffic else None,
                 "algorithmic_work_per_launch": work, "avg_ms": dom_ms, "timed_launches": ncalls,

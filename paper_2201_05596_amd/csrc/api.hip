@@ -135,7 +135,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.h = take(E * C * f * es);
     L.ye = take(E * C * d * es);
     L.hd = take(s->residual ? T * f * es : 0);
-    L.dense = take(s->residual && !plan.mfma ? T * d * es : 0);
+    L.dense = take(s->residual ? T * d * es : 0);      // the dense branch's output where it is not combined in place
     L.partial = take(plan.ksplit2 > 1 ? (size_t)plan.ksplit2 * E * C * d * 4 : 0);
     L.total = off;
     return L;
@@ -317,6 +317,53 @@ int run_dense_branch(const moe_shape_t* s, const void* x, const void* Wd1, const
     prof_pre(ST_DENSE2, st);
     rc = tiled ? launch_tgemm(a, EPI_COMBINE, st) : launch_wsgemm(a, EPI_COMBINE, MT, NW, 2, st);
     prof_mark(ST_DENSE2, st);
+    return rc;
+}
+
+// Residual-MoE with experts and dense branch both on 256-row tiles: the experts' and the dense branch's products of
+// each FFN half share one launch (same inner and outer sizes), so that the second half, with only d_model columns,
+// has twice the tiles and can use the large tile; the combine then is a kernel of its own on the two outputs.
+// Returns MOE_ERR_UNSUPPORTED (nothing launched) when the pair does not fit that pattern.
+int run_residual_paired(const moe_shape_t* s, const FfnPlan& p, const void* x, const int32_t* slot_token,
+                        const int32_t* rows, const int32_t* order, const void* W1, const void* b1, const void* W2,
+                        const void* b2, const void* Wd1, const void* bd1, const void* Wd2, const void* bd2, void* h,
+                        void* hd, void* ye, void* dense_out, const int32_t* expert_idx, const int32_t* slot_idx,
+                        const float* gate_w, void* out, hipStream_t st) {
+    if (!p.tiled || s->T <= 128) return MOE_ERR_UNSUPPORTED;
+    const int packed = s->flags & MOE_FLAG_PACKED_WEIGHTS;
+    WsGemmArgs e1{}, d1{}, e2{}, d2{};
+    e1.A = u16(x); e1.B = u16(W1); e1.bias = u16(b1); e1.rows = rows; e1.order = order; e1.row_map = slot_token;
+    e1.packed = packed; e1.max_rows = s->capacity; e1.map_stride = s->capacity; e1.G = s->E; e1.K = s->d_model;
+    e1.N = s->d_ffn; e1.a_group_stride = s->capacity; e1.out = u16(h); e1.o_group_stride = s->capacity; e1.ksplit = 1;
+    d1.A = u16(x); d1.B = u16(Wd1); d1.bias = u16(bd1); d1.fixed_rows = s->T; d1.max_rows = s->T; d1.G = 1;
+    d1.packed = packed; d1.K = s->d_model; d1.N = s->d_ffn; d1.out = u16(hd); d1.ksplit = 1;
+    e2 = e1; e2.A = u16(h); e2.B = u16(W2); e2.bias = u16(b2); e2.row_map = nullptr; e2.K = s->d_ffn; e2.N = s->d_model;
+    e2.out = u16(ye);
+    d2 = d1; d2.A = u16(hd); d2.B = u16(Wd2); d2.bias = u16(bd2); d2.K = s->d_ffn; d2.N = s->d_model; d2.out = u16(dense_out);
+    if (!tgemm_pair_fusable(e2, d2)) return MOE_ERR_UNSUPPORTED;
+    int rc;
+    if (tgemm_pair_fusable(e1, d1)) {
+        prof_pre(ST_GEMM1, st);
+        rc = launch_tgemm_pair(e1, d1, EPI_GELU, st);
+        prof_mark(ST_GEMM1, st);
+    } else {                                  // the first halves each on the tile that suits them
+        prof_pre(ST_GEMM1, st);
+        rc = launch_tgemm(e1, EPI_GELU, st);
+        prof_mark(ST_GEMM1, st);
+        if (rc != MOE_OK) return rc;
+        prof_pre(ST_DENSE1, st);
+        rc = launch_tgemm(d1, EPI_GELU, st);
+        prof_mark(ST_DENSE1, st);
+    }
+    if (rc != MOE_OK) return rc;
+    prof_pre(ST_GEMM2, st);
+    rc = launch_tgemm_pair(e2, d2, EPI_STORE, st);
+    prof_mark(ST_GEMM2, st);
+    if (rc != MOE_OK) return rc;
+    prof_pre(ST_COMBINE, st);
+    rc = launch_combine(ye, s->dtype, expert_idx, slot_idx, gate_w, dense_out, out, s->T, s->top_k, s->capacity,
+                        s->d_model, st);
+    prof_mark(ST_COMBINE, st);
     return rc;
 }
 
@@ -573,6 +620,12 @@ static int layer_forward_checked(const moe_shape_t* shape, const void* x, const 
         return rc;
     }
 
+    if (shape->residual) {
+        rc = run_residual_paired(shape, plan, x, slot_token, rows, order, W1, b1, W2, b2, Wd1, bd1, Wd2, bd2,
+                                 at<void>(ws, L.h), at<void>(ws, L.hd), at<void>(ws, L.ye), at<void>(ws, L.dense),
+                                 expert_idx, slot_idx, gate_w, out, st);
+        if (rc != MOE_ERR_UNSUPPORTED) return rc;
+    }
     // bf16: dispatch is fused into GEMM-1 (rows gathered through slot_token) ...
     rc = run_expert_gemm1(shape, plan, x, slot_token, rows, order, W1, b1, at<void>(ws, L.h), st);
     if (rc != MOE_OK) return rc;

@@ -69,7 +69,15 @@ template <int WM, int NWM, int NS_, int WN> struct TileCfg {
 };
 
 template <int WM, int NWM, int NSX, int EPI, int WN, bool PACKED>
-__global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a) {
+__global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU)) void tgemm_kernel(const WsGemmArgs a0,
+                                                                                                   const WsGemmArgs a1,
+                                                                                                   const int split) {
+    // One launch may carry two grouped products of the same shape class (the experts' and the dense branch's of a
+    // Residual-MoE layer): work-groups below `split` belong to the first, the others to the second.  Twice the tiles
+    // let products with few columns use the large tile and still give every CU one.
+    const bool second = (int)blockIdx.x >= split;                // uniform over the work-group
+    const WsGemmArgs& a = second ? a1 : a0;
+    const int block = second ? (int)blockIdx.x - split : (int)blockIdx.x;
     typedef TileCfg<WM, NWM, NSX, WN> Cfg;
     constexpr int TBN = Cfg::TBN, NCF = WN / 16;               // column fragments (= columns per lane) of a wave
     constexpr int BM = Cfg::BM, MSUB = WM / 16, NIB = Cfg::NIB, NTHREADS = NWM * 128;
@@ -85,8 +93,8 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
 
     const int n_tiles = (a.N + TBN - 1) / TBN;
     const int m_tiles = (a.max_rows + BM - 1) / BM;
-    const TileId tile = tile_spread(a, n_tiles) ? tile_of_block_spread(a, n_tiles, m_tiles, blockIdx.x)
-                                                : tile_of_block(a, n_tiles, m_tiles, blockIdx.x);
+    const TileId tile = tile_spread(a, n_tiles) ? tile_of_block_spread(a, n_tiles, m_tiles, block)
+                                                : tile_of_block(a, n_tiles, m_tiles, block);
     const int g = tile.g, nt = tile.nt, mt = tile.inner;
 
     if (EPI == EPI_SCATTER) zero_dropped_rows(a, tid, NTHREADS);
@@ -345,12 +353,14 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     }
 }
 
+// b == nullptr: one product; otherwise the two products share the launch (same K, N, packing)
 template <int WM, int NWM, int NSX, int EPI, int WN, bool PACKED>
-static int launch_tp(const WsGemmArgs& a, hipStream_t s) {
+static int launch_tp(const WsGemmArgs& a, const WsGemmArgs* b, hipStream_t s) {
     constexpr int BM = NWM * WM, TBN = 2 * WN;
     const int n_tiles = (a.N + TBN - 1) / TBN;
-    const int m_tiles = (a.max_rows + BM - 1) / BM;
-    const long long blocks = tile_grid_blocks(a, n_tiles, m_tiles);
+    const long long blocks_a = tile_grid_blocks(a, n_tiles, (a.max_rows + BM - 1) / BM);
+    const long long blocks_b = b ? tile_grid_blocks(*b, n_tiles, (b->max_rows + BM - 1) / BM) : 0;
+    const long long blocks = blocks_a + blocks_b;                // both multiples of the XCD count
     if (blocks > (1ll << 30)) return MOE_ERR_UNSUPPORTED;        // block indices are ints in the kernel
     const size_t smem = TileCfg<WM, NWM, NSX, WN>::LDS_BYTES;
     static_assert(TileCfg<WM, NWM, NSX, WN>::LDS_BYTES <= 160 * 1024, "a work-group's ring must fit one CU's LDS");
@@ -363,12 +373,13 @@ static int launch_tp(const WsGemmArgs& a, hipStream_t s) {
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI, WN, PACKED>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a);
+    hipLaunchKernelGGL((tgemm_kernel<WM, NWM, NSX, EPI, WN, PACKED>), dim3((unsigned)blocks), dim3(NWM * 128), smem, s, a,
+                       b ? *b : a, (int)blocks_a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 template <int WM, int NWM, int NSX, int EPI, int WN>
-static int launch_t(const WsGemmArgs& a, hipStream_t s) {
-    return a.packed ? launch_tp<WM, NWM, NSX, EPI, WN, true>(a, s) : launch_tp<WM, NWM, NSX, EPI, WN, false>(a, s);
+static int launch_t(const WsGemmArgs& a, const WsGemmArgs* b, hipStream_t s) {
+    return a.packed ? launch_tp<WM, NWM, NSX, EPI, WN, true>(a, b, s) : launch_tp<WM, NWM, NSX, EPI, WN, false>(a, b, s);
 }
 
 // Tile shapes.  256 x 256 (4 x 2 waves of 64 x 128: the accumulators take 128 registers, which the compiler updates
@@ -387,28 +398,58 @@ static TileShape pick_tile(int max_rows, int G, int N) {
     return TILE_128x256;
 }
 
+// Two products in one launch (same K, N and packing; the tile is picked for the tiles of both together).  Both with
+// groups of more than 128 rows: 256-row tiles, the large 256 x 256 one if the pair has enough tiles for it.  One of
+// them with groups of at most 128 rows: 128 x 256 tiles for both, but only if the other product alone could not fill
+// the chip with 256 x 256 tiles (a product with few columns), since 128-row tiles are the less efficient ones.
+static bool pair_shape(const WsGemmArgs& a, const WsGemmArgs& b, TileShape* shape) {
+    if (a.K != b.K || a.N != b.N || (a.packed != 0) != (b.packed != 0) || a.ksplit != 1 || b.ksplit != 1) return false;
+    const long long n256 = (a.N + 255) / 256;
+    if (a.max_rows <= 128 || b.max_rows <= 128) {
+        const WsGemmArgs& big = a.max_rows <= 128 ? b : a;
+        if (big.max_rows <= 128 || (long long)big.G * ((big.max_rows + 255) / 256) * n256 >= 256) return false;
+        *shape = TILE_128x256;
+        return true;
+    }
+    const long long row_tiles = (long long)a.G * ((a.max_rows + 255) / 256) + (long long)b.G * ((b.max_rows + 255) / 256);
+    if (row_tiles * n256 >= 256) *shape = TILE_256x256;
+    else if (row_tiles * ((a.N + 127) / 128) >= 256) *shape = TILE_256x128;
+    else return false;
+    return true;
+}
+bool tgemm_pair_fusable(const WsGemmArgs& a, const WsGemmArgs& b) {
+    TileShape t;
+    return tgemm_supported(a.K, a.N) && pair_shape(a, b, &t);
+}
+
 template <int EPI>
-static int launch_t_epi(const WsGemmArgs& a, hipStream_t s) {
-    switch (pick_tile(a.max_rows, a.G, a.N)) {
-        case TILE_256x256: return launch_t<64, 4, 4, EPI, 128>(a, s);
-        case TILE_256x128: return launch_t<64, 4, 5, EPI, 64>(a, s);
-        default: return a.K <= 2048 ? launch_t<64, 2, 3, EPI, 128>(a, s) : launch_t<32, 4, 5, EPI, 128>(a, s);
+static int launch_t_epi(const WsGemmArgs& a, const WsGemmArgs* b, hipStream_t s) {
+    TileShape shape = pick_tile(a.max_rows, a.G, a.N);
+    if (b && !pair_shape(a, *b, &shape)) return MOE_ERR_INVALID_ARG;
+    switch (shape) {
+        case TILE_256x256: return launch_t<64, 4, 4, EPI, 128>(a, b, s);
+        case TILE_256x128: return launch_t<64, 4, 5, EPI, 64>(a, b, s);
+        default: return a.K <= 2048 ? launch_t<64, 2, 3, EPI, 128>(a, b, s) : launch_t<32, 4, 5, EPI, 128>(a, b, s);
     }
 }
 
 bool tgemm_supported(int K, int N) { return K % kTK == 0 && K >= kTK && N % 8 == 0 && N >= 8; }
 
-int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s) {
-    if (a.G <= 0 || a.max_rows <= 0) return MOE_OK;
+static int launch_tgemm_any(const WsGemmArgs& a, const WsGemmArgs* b, int epi, hipStream_t s) {
+    if (a.G <= 0 || a.max_rows <= 0) return b ? MOE_ERR_INVALID_ARG : MOE_OK;
     if (a.ksplit != 1 || !tgemm_supported(a.K, a.N)) return MOE_ERR_INVALID_ARG;
     switch (epi) {
-        case EPI_STORE: return launch_t_epi<EPI_STORE>(a, s);
-        case EPI_GELU: return launch_t_epi<EPI_GELU>(a, s);
-        case EPI_SCATTER: return launch_t_epi<EPI_SCATTER>(a, s);
-        case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, s);
-        case EPI_PARTIAL: return launch_t_epi<EPI_PARTIAL>(a, s);      // ksplit == 1: one fp32 partial, no bias
+        case EPI_STORE: return launch_t_epi<EPI_STORE>(a, b, s);
+        case EPI_GELU: return launch_t_epi<EPI_GELU>(a, b, s);
+        case EPI_SCATTER: return b ? MOE_ERR_INVALID_ARG : launch_t_epi<EPI_SCATTER>(a, b, s);   // zeroes rows grid-wide
+        case EPI_COMBINE: return launch_t_epi<EPI_COMBINE>(a, b, s);
+        case EPI_PARTIAL: return launch_t_epi<EPI_PARTIAL>(a, b, s);      // ksplit == 1: one fp32 partial, no bias
         default: return MOE_ERR_INVALID_ARG;
     }
+}
+int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s) { return launch_tgemm_any(a, nullptr, epi, s); }
+int launch_tgemm_pair(const WsGemmArgs& a, const WsGemmArgs& b, int epi, hipStream_t s) {
+    return launch_tgemm_any(a, &b, epi, s);
 }
 
 }  // namespace moe

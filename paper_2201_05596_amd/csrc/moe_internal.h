@@ -177,6 +177,9 @@ int wsgemm_chunk_k(int MT);
 
 // Tiled variant for groups with many rows (ffn_tile.hip); same arguments, ksplit must be 1.
 int launch_tgemm(const WsGemmArgs& a, int epi, hipStream_t s);
+// two grouped products in one launch (same K, N, packing, epilogue; both with 256-row tiles): twice the tiles
+bool tgemm_pair_fusable(const WsGemmArgs& a, const WsGemmArgs& b);
+int launch_tgemm_pair(const WsGemmArgs& a, const WsGemmArgs& b, int epi, hipStream_t s);
 bool tgemm_supported(int K, int N);   // K a multiple of 32   // k-extent of one LDS chunk = granularity of split-K
 
 // Weights in the fragment order of v_mfma_f32_16x16x32_bf16's second operand (pack.hip).  Element (k, n) of group g
