@@ -299,6 +299,8 @@ REDUCED = {
     # same structure as the full configurations, fewer experts/tokens so the fp64 oracle stays fast
     "c2r": CONFIGS["c2"].scaled(name="c2r", T=1000, E=16, capacity_factor=1.0),
     "c3r": CONFIGS["c3a"].scaled(name="c3r", T=900, E=8, d_ffn=2048),
+    # Residual-MoE whose expert and dense products pair up on 256 x 128 tiles (48 row tiles of 256: too few for 256 x 256)
+    "c3p": CONFIGS["c3a"].scaled(name="c3p", T=4100, E=16, d_ffn=2048),
     "c4r": CONFIGS["c4"].scaled(name="c4r", E=32, d_ffn=4096),
     "c5r": CONFIGS["c5"].scaled(name="c5r", T=1100, E=8, d_model=512, d_ffn=2048),
 }
