@@ -51,8 +51,8 @@ ALL_CONFIGS = ("c2", "c3a", "c3b", "c4", "c5")
 # (profiles/*.md name the commands), not in this process.
 PROFILED_TRAFFIC = {          # profiles/hbm_traffic_all_configs.md
     ("c2", "expert_gemm1"): 1161700000, ("c2", "expert_gemm2"): 1162500000,
-    ("c3a", "expert_gemm2"): 348900000, ("c3a", "expert_gemm1"): 283900000,
-    ("c3b", "expert_gemm1"): 617200000, ("c3b", "expert_gemm2"): 617200000,
+    ("c3a", "expert_gemm2"): 500000000, ("c3a", "expert_gemm1"): 583500000,       # experts + dense branch, one launch
+    ("c3b", "expert_gemm1"): 617200000, ("c3b", "expert_gemm2"): 769000000,       # GEMM-2: experts + dense branch
     ("c4", "expert_gemm1"): 1628100000, ("c4", "expert_gemm2"): 1613400000,
     ("c5", "expert_gemm1"): 9231000000, ("c5", "expert_gemm2"): 10946900000,
 }
