@@ -129,7 +129,7 @@ WsLayout ws_layout(const moe_shape_t* s) {
     L.slot_idx = take(T * k * 4);
     L.gate_w = take(T * k * 4);
     L.rows = take(E * 4);
-    L.order = take((E + 1) * 4);      // launch order of the experts + the tile-dealing flag
+    L.order = take(2 * (E + 1) * 4);  // two launch orders of the experts, each followed by the tile-dealing flag
     L.slot_token = take(E * C * 4);
     L.xe = take(plan.mfma ? 0 : E * C * d * es);       // the MFMA path gathers rows inside GEMM-1
     L.h = take(E * C * f * es);
@@ -265,7 +265,11 @@ int run_expert_gemm2(const moe_shape_t* s, const FfnPlan& p, const void* h, cons
                      const int32_t* order, const void* W2, const void* b2, bool scatter, const int32_t* slot_token, const int32_t* slot_idx,
                      const float* gate_w, void* dst, float* partial, hipStream_t st) {
     WsGemmArgs a{};
-    a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.order = order; a.row_map = nullptr;
+    a.A = u16(h); a.B = u16(W2); a.bias = u16(b2); a.rows = rows; a.row_map = nullptr;
+    // The tiled kernel's tiles of this product are long (K = d_ffn) and few per CU: the busiest experts go first, so
+    // that the short tiles of the light ones fill the end (the second list).  GEMM-1 and the streaming kernel keep
+    // the list that alternates busy and light experts.
+    a.order = order && p.tiled ? order + s->E + 1 : order;
     a.packed = s->flags & MOE_FLAG_PACKED_WEIGHTS;
     a.max_rows = s->capacity; a.G = s->E; a.K = s->d_ffn; a.N = s->d_model;
     a.a_group_stride = s->capacity; a.out = u16(dst); a.o_group_stride = s->capacity; a.ksplit = p.ksplit2;

@@ -95,7 +95,7 @@ size_t route_scratch_ints(int T, int E, int k);
 // softmax + top-k + capacity slots from fp32 logits
 int launch_route(const float* logits, int T, int E, int k, int C,
                  int32_t* expert_idx, int32_t* slot_idx, float* gate_w,
-                 int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order /* [E] or nullptr */,
+                 int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order /* [2E + 2] or nullptr */,
                  int32_t* scratch, hipStream_t s);
 
 // second routing kernel alone: hist = one histogram [k][E] per block of TB tokens (TB divides 256) with the
@@ -104,7 +104,7 @@ int launch_route_finalize(int T, int E, int k, int C, int TB, const int32_t* exp
                           int32_t* expert_rows, int32_t* slot_token, int32_t* expert_order, const int32_t* hist,
                           hipStream_t s);
 
-// order[rank] = expert, ranked by min(expert_rows, C) descending (ties by index)
+// the two launch orders of the experts (2E + 2 ints: see write_expert_order) from the row counts alone
 int launch_expert_order(const int32_t* expert_rows, int E, int C, int32_t* order, hipStream_t s);
 
 int launch_dispatch(const void* x, int dtype, const int32_t* slot_token, const int32_t* expert_rows,

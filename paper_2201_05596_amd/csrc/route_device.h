@@ -141,7 +141,9 @@ __device__ __forceinline__ void route_local_body(int32_t* smem, const float* __r
 // order[E] (one entry past the list) tells the tiled GEMM how to deal its tiles to the XCDs: 1 when the active
 // experts are of very different sizes (at least a quarter of them hold at most a quarter of the largest one's
 // rows), so that dealing whole experts would leave the XCDs with unequal work; 0 otherwise.
-// `sorted` is LDS scratch of E + 2 ints; every thread of the block must call.
+// A second list follows at order[E + 1 ..]: the experts plainly by rows, busiest first, and the same flag at
+// order[2E + 1] (for products whose tiles are long and few per compute unit: longest first, short ones fill the end).
+// `order` holds 2E + 2 ints.  `sorted` is LDS scratch of E + 2 ints; every thread of the block must call.
 __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */, int E, int32_t* __restrict__ order,
                                                    int32_t* sorted /* LDS */, int tid, int nthreads) {
     if (tid == 0) sorted[E] = sorted[E + 1] = 0;
@@ -184,7 +186,7 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
         for (int e = tid; e < E; e += nthreads) small += rows[e] > 0 && rows[e] * 4 <= largest ? 1 : 0;
         if (small) atomicAdd(&sorted[E + 1], small);
         __syncthreads();
-        if (tid == 0) order[E] = sorted[E + 1] * 4 >= na && na > 0 ? 1 : 0;
+        if (tid == 0) order[E] = order[2 * E + 1] = sorted[E + 1] * 4 >= na && na > 0 ? 1 : 0;
     }
     for (int p = tid; p < E; p += nthreads) {
         int e;
@@ -198,6 +200,7 @@ __device__ __forceinline__ void write_expert_order(const int32_t* rows /* LDS */
             e = ((j + x) & 1) ? sorted[na - 1 - light_before] : sorted[busy_before];
         }
         order[p] = e;
+        order[E + 1 + p] = sorted[p];                     // second list: plainly by rows, busiest first
     }
 }
 
