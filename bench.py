@@ -207,6 +207,30 @@ def time_decode_block(steps, warmup, pack):
             "hbm_frac": bytes_alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
 
+def time_library_gemm(steps, warmup):
+    """Context only, never part of a step: the vendor's bf16 GEMM (torch.matmul) on the dense products whose shapes
+    the prefill workloads' FFN halves have, on this GPU and at the same clock state as the timed layers.  What this
+    library reaches on a product is the practical mark for a hand-written tile kernel on the same machine."""
+    import torch
+    out = []
+    for M, K, N in ((8192, 4096, 4096), (8192, 1024, 4096), (8192, 4096, 1024), (16384, 4096, 16384)):
+        a = torch.randn(M, K, device="cuda:0", dtype=torch.bfloat16)
+        b = torch.randn(K, N, device="cuda:0", dtype=torch.bfloat16) * 0.02
+        c = torch.empty(M, N, device="cuda:0", dtype=torch.bfloat16)
+        for _ in range(RAMP_STEPS + warmup):
+            torch.matmul(a, b, out=c)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            torch.matmul(a, b, out=c)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        out.append({"M": M, "K": K, "N": N, "us": us, "TFLOPs": 2.0 * M * K * N / us / 1e6,
+                    "mfma_frac": 2.0 * M * K * N / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
+        del a, b, c
+    return out
+
+
 def cpu_baseline(inp, cfg, rows, budget_s=12.0):
     """The oracle as it stands on the host cores, on a bounded sample of the workload: the gate, the dispatch and
     the combine on all tokens, the expert FFNs on every n-th touched expert (by row count, busiest first) until the
@@ -269,6 +293,9 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library's bf16 GEMM on the prefill workloads' dense product shapes "
+                         "(extras.library_gemm: context for the tiled kernel's rate, not part of any step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -301,6 +328,8 @@ def main() -> int:
     head, inp, rows = time_config(head_cfg, args.steps, args.warmup, not args.plain_weights)
     configs[head_cfg.name] = head
 
+    if args.library_gemm:
+        extras["library_gemm"] = time_library_gemm(SUB_STEPS, args.warmup)
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
