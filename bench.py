@@ -177,12 +177,14 @@ def time_decode_block(steps, warmup, pack):
     bi = make_block_inputs(cfg, heads, max_len, "cuda:0", bias_std=0.0, pos_mode="full")
     lay = bi.layer
     T, d, f, E = cfg.T, cfg.d_model, cfg.d_ffn, cfg.E
-    shape = moe.make_shape(T, d, f, E, cfg.top_k, cfg.capacity, "bf16", flags=moe.MOE_FLAG_PACKED_WEIGHTS if pack else 0)
+    packed_gate = moe.moe_pack_gate(lay.Wg) if pack else None
+    flags = (moe.MOE_FLAG_PACKED_WEIGHTS if pack else 0) | (moe.MOE_FLAG_PACKED_GATE if packed_gate is not None else 0)
+    shape = moe.make_shape(T, d, f, E, cfg.top_k, cfg.capacity, "bf16", flags=flags)
     block = moe.MoeBlockShape(heads, max_len)
     ws = torch.empty(moe.moe_decode_block_workspace_bytes(shape, block), dtype=torch.uint8, device="cuda:0")
     pk = moe.moe_pack_weights if pack else (lambda w: w)
     weights = dict(ln1_gamma=bi.ln1_gamma, ln1_beta=bi.ln1_beta, Wqkv=bi.Wqkv, bqkv=bi.bqkv, Wo=bi.Wo, bo=bi.bo,
-                   ln2_gamma=bi.ln2_gamma, ln2_beta=bi.ln2_beta, Wg=lay.Wg, bg=lay.bg, W1=pk(lay.W1), b1=lay.b1,
+                   ln2_gamma=bi.ln2_gamma, ln2_beta=bi.ln2_beta, Wg=packed_gate if packed_gate is not None else lay.Wg, bg=lay.bg, W1=pk(lay.W1), b1=lay.b1,
                    W2=pk(lay.W2), b2=lay.b2)
     out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda:0")
     logits = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
@@ -293,6 +295,8 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
+    ap.add_argument("--decode-block", action="store_true",
+                    help="with --only: time the decode block (extras.decode_block_c4) as well")
     ap.add_argument("--library-gemm", action="store_true",
                     help="also time the vendor library's bf16 GEMM on the prefill workloads' dense product shapes "
                          "(extras.library_gemm: context for the tiled kernel's rate, not part of any step)")
@@ -325,6 +329,9 @@ def main() -> int:
         torch.cuda.empty_cache()
     else:
         extras = {}
+        if args.decode_block:
+            extras["decode_block_c4"] = time_decode_block(SUB_STEPS, args.warmup, not args.plain_weights)
+            torch.cuda.empty_cache()
     head, inp, rows = time_config(head_cfg, args.steps, args.warmup, not args.plain_weights)
     configs[head_cfg.name] = head
 

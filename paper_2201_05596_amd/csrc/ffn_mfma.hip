@@ -308,7 +308,7 @@ __global__ __launch_bounds__(NW * 64) void wsgemm_kernel(const WsGemmArgs a, con
 
 // ------------------------------------------------------------------------------------------
 // Split-K finish: out = epilogue( sum_s partial[s] + bias ), splits summed in index order so the
-// result does not depend on scheduling.  One wave per expert row.
+// result does not depend on scheduling.  One wave per expert row and 512-column piece of it.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const SplitKReduceArgs a) {
     const int lane = threadIdx.x & 63;
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -322,9 +322,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const SplitKReduceAr
             }
         }
     }
-    for (long long row = wave; row < total_rows; row += nwaves) {
+    // one wave per (row, 512-column piece): few rows (a decode step) still spread over the chip
+    const int pieces = (a.N / 8 + 63) / 64;
+    for (long long item = wave; item < total_rows * pieces; item += nwaves) {
+        const long long row = item / pieces;
+        const int i = (int)(item % pieces) * 64 + lane;
         const int g = (int)(row / a.group_stride), r = (int)(row % a.group_stride);
-        if (r >= (a.rows ? min(a.rows[g], a.max_rows) : a.max_rows)) continue;
+        if (r >= (a.rows ? min(a.rows[g], a.max_rows) : a.max_rows) || i >= a.N / 8) continue;
         float gw = 1.f;
         size_t orow = (size_t)row;
         if (a.scatter_map) {
@@ -332,34 +336,49 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const SplitKReduceAr
             gw = a.gate_w[(size_t)t * a.top_k];
             orow = (size_t)t;
         }
-        for (int i = lane; i < a.N / 8; i += 64) {
-            float v[8];
+        float v[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = 0.f;
-            for (int s = 0; s < a.ksplit; ++s) {
-                const float* p = a.partial + ((size_t)s * total_rows + row) * a.N + (size_t)i * 8;
-                const float4 x0 = *reinterpret_cast<const float4*>(p), x1 = *reinterpret_cast<const float4*>(p + 4);
-                v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
-                v[4] += x1.x; v[5] += x1.y; v[6] += x1.z; v[7] += x1.w;
+        for (int q = 0; q < 8; ++q) v[q] = 0.f;
+        const float* p0 = a.partial + (size_t)row * a.N + (size_t)i * 8;
+        const size_t sstride = (size_t)total_rows * a.N;
+        int s = 0;
+        for (; s + 4 <= a.ksplit; s += 4) {                     // four splits' loads in flight, summed in split order
+            float4 x0[4], x1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float* p = p0 + (size_t)(s + u) * sstride;
+                x0[u] = *reinterpret_cast<const float4*>(p);
+                x1[u] = *reinterpret_cast<const float4*>(p + 4);
             }
-            if (a.bias) {
-                const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + (size_t)i * 8);
-                v[0] += __uint_as_float(bv.x << 16); v[1] += __uint_as_float(bv.x & 0xffff0000u);
-                v[2] += __uint_as_float(bv.y << 16); v[3] += __uint_as_float(bv.y & 0xffff0000u);
-                v[4] += __uint_as_float(bv.z << 16); v[5] += __uint_as_float(bv.z & 0xffff0000u);
-                v[6] += __uint_as_float(bv.w << 16); v[7] += __uint_as_float(bv.w & 0xffff0000u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v[0] += x0[u].x; v[1] += x0[u].y; v[2] += x0[u].z; v[3] += x0[u].w;
+                v[4] += x1[u].x; v[5] += x1[u].y; v[6] += x1[u].z; v[7] += x1[u].w;
             }
-            uint4 o;
-            o.x = pack_bf16x2(gw * v[0], gw * v[1]); o.y = pack_bf16x2(gw * v[2], gw * v[3]);
-            o.z = pack_bf16x2(gw * v[4], gw * v[5]); o.w = pack_bf16x2(gw * v[6], gw * v[7]);
-            *reinterpret_cast<uint4*>(a.out + orow * a.N + (size_t)i * 8) = o;
         }
+        for (; s < a.ksplit; ++s) {
+            const float* p = p0 + (size_t)s * sstride;
+            const float4 x0 = *reinterpret_cast<const float4*>(p), x1 = *reinterpret_cast<const float4*>(p + 4);
+            v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
+            v[4] += x1.x; v[5] += x1.y; v[6] += x1.z; v[7] += x1.w;
+        }
+        if (a.bias) {
+            const uint4 bv = *reinterpret_cast<const uint4*>(a.bias + (size_t)g * a.N + (size_t)i * 8);
+            v[0] += __uint_as_float(bv.x << 16); v[1] += __uint_as_float(bv.x & 0xffff0000u);
+            v[2] += __uint_as_float(bv.y << 16); v[3] += __uint_as_float(bv.y & 0xffff0000u);
+            v[4] += __uint_as_float(bv.z << 16); v[5] += __uint_as_float(bv.z & 0xffff0000u);
+            v[6] += __uint_as_float(bv.w << 16); v[7] += __uint_as_float(bv.w & 0xffff0000u);
+        }
+        uint4 o;
+        o.x = pack_bf16x2(gw * v[0], gw * v[1]); o.y = pack_bf16x2(gw * v[2], gw * v[3]);
+        o.z = pack_bf16x2(gw * v[4], gw * v[5]); o.w = pack_bf16x2(gw * v[6], gw * v[7]);
+        *reinterpret_cast<uint4*>(a.out + orow * a.N + (size_t)i * 8) = o;
     }
 }
 
 int launch_splitk_reduce(const SplitKReduceArgs& a, hipStream_t s) {
     const long long total_rows = (long long)a.G * a.group_stride;
-    long long blocks = (total_rows + 3) / 4;
+    long long blocks = (total_rows * ((a.N / 8 + 63) / 64) + 3) / 4;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
