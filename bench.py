@@ -54,7 +54,7 @@ PROFILED_TRAFFIC = {          # profiles/hbm_traffic_all_configs.md
     ("c3a", "expert_gemm2"): 500000000, ("c3a", "expert_gemm1"): 583500000,       # experts + dense branch, one launch
     ("c3b", "expert_gemm1"): 617200000, ("c3b", "expert_gemm2"): 769000000,       # GEMM-2: experts + dense branch
     ("c4", "expert_gemm1"): 1628100000, ("c4", "expert_gemm2"): 1613400000,
-    ("c5", "expert_gemm1"): 9231000000, ("c5", "expert_gemm2"): 10946900000,
+    ("c5", "expert_gemm1"): 9341700000, ("c5", "expert_gemm2"): 11142800000,
 }
 
 
