@@ -29,6 +29,10 @@
  *     run concurrently on different streams race.
  *   - Entry points are called from one host thread at a time (the library
  *     keeps small host-side caches: kernel attributes, occupancy, profiler).
+ *   - Stream capture: after one ordinary call with the same shape (kernel
+ *     attributes and occupancy are looked up at first use) a call only
+ *     enqueues kernels and may be recorded into a HIP graph; every replay
+ *     gives what the ordinary call gives.  Keep the stage profiler off then.
  */
 #ifndef MOE_H_
 #define MOE_H_

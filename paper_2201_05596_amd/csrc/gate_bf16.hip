@@ -305,8 +305,9 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
 // The whole gate of a decode step (at most 256 tokens) in ONE launch: the work-groups compute the logits tile by tile
 // (experts split over work-groups, so that many CUs share the read of the gate weights); every work-group then
 // publishes a flag, and the one with the highest index waits for all flags and runs the whole routing on the finished
-// logits.  The flags hold the call's epoch (a number the host never repeats for a workspace), so they need no
-// clearing: whatever an earlier call or nobody left there is not this call's epoch.  Hand-over across the XCDs'
+// logits.  The flags hold the call's epoch (never 0, and not repeated by the host from one call to the next), so they
+// need no clearing beforehand: what nobody or an earlier call left there is not this call's epoch, and the waiting
+// work-group puts every flag it has seen back to 0, which also makes a replayed graph launch (same epoch) safe.  Hand-over across the XCDs'
 // separate L2s: the writers release at device scope after their stores (write-back of the L2), the reader acquires at
 // device scope before its loads (invalidate).  The wait cannot hang: work-groups are started in index order, so all
 // others are running or done when the last one starts (and the whole grid, at most 64 work-groups, fits on the chip
@@ -336,6 +337,9 @@ __global__ __launch_bounds__(256) void gate_decode_kernel(const uint16_t* __rest
         }
     }
     __atomic_thread_fence(__ATOMIC_ACQUIRE);           // device scope: nothing read below comes from a stale cache line
+    // Each flag goes back to 0 (never an epoch) once it has been seen: a captured launch that is replayed carries the
+    // same epoch every time and must not find it in the flags of its own previous run.
+    if ((int)threadIdx.x < nblocks) __hip_atomic_store(flags + threadIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     route_single_body<RK, NV>(reinterpret_cast<int32_t*>(lds), logits, T, E, C, expert_idx, slot_idx, gate_w, expert_rows,
                               slot_token, expert_order, nullptr);
