@@ -58,3 +58,59 @@ def test_layer_forward_replays_like_eager(case, pack):
         assert torch.equal(graphed.out, want), f"replay {i}: output differs from the eager call"
         for name in ("logits", "expert_idx", "slot_idx", "gate_w", "expert_rows", "slot_token"):
             assert torch.equal(graphed.routing[name], eager.routing[name]), f"replay {i}: {name}"
+
+
+@pytest.mark.parametrize("pack", [False, True])
+def test_decode_block_replays_like_eager(pack):
+    """One decode step of the whole block, captured: twelve launches per replay, the decode gate among them.  A replay
+    writes the same key/value rows into the cache again (same positions), so cache and outputs must equal the eager
+    call's bit for bit."""
+    from workloads import make_block_inputs
+    m = U.amd()
+    cfg = CONFIGS["c4"].scaled(name="g-block", T=48, d_model=256, d_ffn=512, E=16)
+    bi = make_block_inputs(cfg, n_heads=4, max_len=600, device=DEV, pos_mode="mixed")
+    lay = bi.layer
+    T, d, E = cfg.T, cfg.d_model, cfg.E
+    shape = m.make_shape(T, d, cfg.d_ffn, E, cfg.top_k, cfg.capacity, "bf16",
+                         flags=m.MOE_FLAG_PACKED_WEIGHTS if pack else 0)
+    block = m.MoeBlockShape(bi.n_heads, bi.max_len)
+    pk = (lambda w: m.moe_pack_weights(w)) if pack else (lambda w: w)
+    weights = dict(ln1_gamma=bi.ln1_gamma, ln1_beta=bi.ln1_beta, Wqkv=bi.Wqkv, bqkv=bi.bqkv, Wo=bi.Wo, bo=bi.bo,
+                   ln2_gamma=bi.ln2_gamma, ln2_beta=bi.ln2_beta, Wg=lay.Wg, bg=lay.bg, W1=pk(lay.W1), b1=lay.b1,
+                   W2=pk(lay.W2), b2=lay.b2)
+
+    def buffers():
+        bf = torch.bfloat16
+        return dict(ws=torch.empty(m.moe_decode_block_workspace_bytes(shape, block), dtype=torch.uint8, device=DEV),
+                    out=torch.empty((T, d), dtype=bf, device=DEV), x1=torch.empty((T, d), dtype=bf, device=DEV),
+                    moe_in=torch.empty((T, d), dtype=bf, device=DEV),
+                    logits=torch.empty((T, E), dtype=torch.float32, device=DEV),
+                    kc=bi.k_cache.clone(), vc=bi.v_cache.clone())
+
+    def run(b, x):
+        m.moe_decode_block_forward(shape, block, weights, x, b["kc"], b["vc"], bi.pos, b["out"], b["x1"], b["moe_in"],
+                                   b["logits"], b["ws"])
+
+    e, g_ = buffers(), buffers()
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    xs = [lay.x] + [torch.randn(lay.x.shape, generator=gen, device=DEV).to(lay.x.dtype) for _ in range(2)]
+    x_static = xs[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(g_, x_static)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(g_, x_static)
+    torch.cuda.synchronize()
+    for i, x in enumerate(xs + xs[:1]):
+        print(f"block replay {i} pack={pack}", flush=True)
+        x_static.copy_(x)
+        graph.replay()
+        torch.cuda.synchronize()
+        run(e, x)
+        torch.cuda.synchronize()
+        for name in ("out", "x1", "moe_in", "logits", "kc", "vc"):
+            assert torch.equal(g_[name], e[name]), f"replay {i}: {name}"
