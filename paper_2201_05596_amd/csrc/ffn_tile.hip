@@ -244,21 +244,6 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
         }
     };
 
-    // The bias is fetched now, ahead of every stage load (loads complete in order, so the counted waits below hold as
-    // they are), instead of costing the epilogue a memory round trip.
-    // packed weights, 64-column waves: wave wn holds fragments 4wn..4wn+3 of the tile's one 128-column group,
-    // i.e. columns 8c + 4wn + i of it
-    const int n_lane = PACKED && WN == 64 ? n0 + c * 8 + wn * 4 : n0 + wn * WN + c * NCF;
-    uint4 bias_raw = make_uint4(0, 0, 0, 0);
-    if (ACT > 0 && n_lane < a.N && a.bias) {
-        const uint16_t* bp = a.bias + (size_t)g * a.N + n_lane;
-        if (NCF == 8) bias_raw = *reinterpret_cast<const uint4*>(bp);
-        else {
-            const uint2 bv = *reinterpret_cast<const uint2*>(bp);      // 4 columns: 8 bytes of bias
-            bias_raw.x = bv.x; bias_raw.y = bv.y;
-        }
-    }
-
     // ---- main loop ---------------------------------------------------------------------------------
     // In step s the fragments of stage s are already in registers; the step waits for this wave's
     // share of stage s+1 (in-order completion: NS-3 later stages may stay outstanding), meets the
@@ -303,11 +288,23 @@ __global__ __launch_bounds__(NWM * 128, (TileCfg<WM, NWM, NSX, WN>::WGS_PER_CU))
     wait_vmcnt<0>();                      // drain the over-issued tail loads before LDS is released
 
     // ---- epilogue ------------------------------------------------------------------------------
+    // packed weights, 64-column waves: wave wn holds fragments 4wn..4wn+3 of the tile's one 128-column group,
+    // i.e. columns 8c + 4wn + i of it
+    const int n_lane = PACKED && WN == 64 ? n0 + c * 8 + wn * 4 : n0 + wn * WN + c * NCF;
     if (ACT == 0 || n_lane >= a.N) return;
     float bias[NCF];
     {
         float b8[8];
-        unpack_bias8(bias_raw, b8);                                  // NCF == 4: the upper four are zeros, unused
+        if (NCF == 8) load_bias8(a, g, n_lane, b8);
+        else {                                                   // 4 columns: 8 bytes of bias
+#pragma unroll
+            for (int i = 0; i < 8; ++i) b8[i] = 0.f;
+            if (a.bias) {
+                const uint2 bv = *reinterpret_cast<const uint2*>(a.bias + (size_t)g * a.N + n_lane);
+                b8[0] = __uint_as_float(bv.x << 16); b8[1] = __uint_as_float(bv.x & 0xffff0000u);
+                b8[2] = __uint_as_float(bv.y << 16); b8[3] = __uint_as_float(bv.y & 0xffff0000u);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < NCF; ++i) bias[i] = b8[i];
     }
